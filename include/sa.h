@@ -1,0 +1,122 @@
+/*
+ * libsa -- Stochastic Attention (SA) hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * What the library computes (paper: "Stochastic Attention", Sec. 3.3, Sec. 3.4, App. B):
+ *   SA:   permute tokens with a sampled permutation, run windowed softmax attention in the permuted
+ *         order, put the outputs back (Alg. 1).  Equivalently (Eq. 3, Eq. 4) every query i attends to
+ *         the keys j whose SLOTS are within the window of i's slot, and -- for causal language
+ *         models -- whose ORIGINAL position is not after i (Sec. 3.3, App. B "stochastic attention
+ *         mask").
+ *   SWA:  the same with the identity permutation (Eq. 1).
+ *   Gated SA+SWA: Y = sigmoid(gamma_sa) * Y_sa + sigmoid(gamma_swa) * Y_swa (Eq. 5), with the gate
+ *         LOGITS supplied by the caller.
+ *   Backward of all of the above (the paper trains through it, Sec. 4.1 / Table 3).
+ * The permuted copies of Q, K, V are never materialised: rows are read through the index tensor
+ * and written back through it.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers owned by the caller, contiguous row-major, 16-byte
+ *     aligned: Q, Y, dY, dQ, Y_sa, Y_swa [B,Hq,n,d]; K, V, dK, dV [B,Hkv,n,d]; LSE [B,Hq,n] float.
+ *     Query head hq uses kv head hq / (Hq/Hkv).
+ *   - perm: int32 [perm_B, perm_H, n]; perm[..., p] is the ORIGINAL index of the token placed at
+ *     permuted slot p (the index tensor of "Q[sigma]" in Sec. 3.3; it is the inverse of the map
+ *     sigma(i) = slot of token i used in Eq. 3).  perm_B in {1,B}, perm_H in {1,Hq}.  NULL means the
+ *     identity.  Each slice must be a bijection of 0..n-1; otherwise results are undefined (use
+ *     sa_check_perm to verify).
+ *   - LSE is the natural-log sum of exp(scale * <q,k>) over the visible keys, in ORIGINAL order.
+ *   - The library allocates no device memory and keeps no state; work is only enqueued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream).  Outputs are overwritten.
+ *   - Every function returns an sa_status.  Argument errors are found on the host before anything
+ *     is launched; nothing aborts or throws.
+ */
+#ifndef SA_H
+#define SA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SA_OK = 0,
+  SA_ERR_NULL = 1,        /* a required pointer is NULL                       */
+  SA_ERR_SHAPE = 2,       /* inconsistent or non-positive sizes               */
+  SA_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for       */
+  SA_ERR_WORKSPACE = 4,   /* workspace missing or smaller than required       */
+  SA_ERR_BAD_PERM = 5,    /* sa_check_perm found a slice that is no bijection */
+  SA_ERR_HIP = 6          /* a HIP call or launch failed                      */
+} sa_status;
+
+typedef enum { SA_BF16 = 0, SA_F32 = 1 } sa_dtype;
+
+/* Window between two SLOTS s (query) and t (key) in permuted order. */
+typedef enum {
+  SA_WIN_SYM_CIRCULAR = 0, /* 2*min(|s-t|, n-|s-t|) < w : Sec. 3.1 / Eq. 3 / App. B (SA default) */
+  SA_WIN_SYM_LINEAR = 1,   /* 2*|s-t| < w               : same without the wrap-around           */
+  SA_WIN_ONE_SIDED = 2     /* 0 <= s-t <= w-1           : Sec. 3.1 footnote (causal SWA default) */
+} sa_window;
+
+typedef struct {
+  int32_t B, Hq, Hkv, n, d; /* Hq % Hkv == 0; d in {64,128}                                   */
+  int32_t w;                /* window size >= 1; may exceed n                                  */
+  int32_t window;           /* sa_window                                                       */
+  int32_t causal_orig;      /* 1: also require original index of key <= that of query (App. B) */
+  int32_t dtype;            /* sa_dtype of Q,K,V,Y,dY,dQ,dK,dV                                 */
+  float scale;              /* softmax scale; <= 0 selects 1/sqrt(d) (Eq. 1)                   */
+  int32_t perm_B, perm_H;   /* perm is [perm_B, perm_H, n]                                     */
+  int32_t gate_per_dim;     /* 0: gate logits [B,Hq,n]; 1: [B,Hq,n,d] (Eq. 5 is per dimension) */
+  int32_t gate_dtype;       /* sa_dtype of the gate logits and of their gradients              */
+} sa_desc;
+
+typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BWD = 3,
+               SA_OP_CHECK_PERM = 4 } sa_op;
+
+const char* sa_status_string(sa_status s);
+
+/* Bytes of device workspace `op` needs for this descriptor (0 if none).  Returns 0 for an invalid
+ * descriptor as well; the entry points report that case. */
+size_t sa_workspace_bytes(const sa_desc* desc, int op);
+
+/* Verifies on the device that every slice of perm is a bijection of 0..n-1.  Synchronises the
+ * stream.  ws: device workspace of sa_workspace_bytes(desc, SA_OP_CHECK_PERM) bytes. */
+sa_status sa_check_perm(const sa_desc* desc, const int32_t* perm, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/* Alg. 1 (Sec. 3.3) with the mask of App. B:  Y = unpermute(windowed_attention(permute(Q,K,V))).
+ * perm NULL = identity.  LSE may be NULL.  ws is unused (may be NULL). */
+sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
+                 const int32_t* perm, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
+sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
+                  void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 2 / Eq. 5 with the gate logits as inputs.  `sa` and `swa` describe the masks of the two
+ * branches and must agree in every other field.  gate_sa / gate_swa: logits, [B,Hq,n] or
+ * [B,Hq,n,d] per sa->gate_per_dim, of sa->gate_dtype.
+ * Y_sa, Y_swa (branch outputs, needed by the backward), LSE_sa, LSE_swa may each be NULL. */
+sa_status gated_sa_swa_fwd(const sa_desc* sa, const sa_desc* swa,
+                           const void* Q, const void* K, const void* V, const int32_t* perm,
+                           const void* gate_sa, const void* gate_swa,
+                           void* Y, void* Y_sa, void* Y_swa, float* LSE_sa, float* LSE_swa,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of sa_fwd (swa == NULL) or of gated_sa_swa_fwd (swa != NULL).
+ * Ungated: Y_sa and LSE_sa are the forward's Y and LSE; gate_*, Y_swa, LSE_swa, dgate_* are
+ * ignored (may be NULL).  Gated: all of them are required.
+ * dQ [B,Hq,n,d], dK, dV [B,Hkv,n,d] (summed over the query heads of a group), dgate_* like the
+ * logits; all overwritten.  ws: sa_workspace_bytes(sa, SA_OP_BWD or SA_OP_GATED_BWD) bytes. */
+sa_status sa_bwd(const sa_desc* sa, const sa_desc* swa,
+                 const void* Q, const void* K, const void* V, const int32_t* perm,
+                 const void* gate_sa, const void* gate_swa,
+                 const void* Y_sa, const void* Y_swa, const float* LSE_sa, const float* LSE_swa,
+                 const void* dY,
+                 void* dQ, void* dK, void* dV, void* dgate_sa, void* dgate_swa,
+                 void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SA_H */

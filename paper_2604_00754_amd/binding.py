@@ -1,0 +1,129 @@
+"""Thin Python binding of libsa's C ABI (include/sa.h): argument marshalling only.
+
+Every step of the path runs inside the HIP library; torch is used for device memory and streams.
+There is no fallback: if libsa.so is missing the import of this module fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsa.so")
+
+SA_OK, SA_ERR_NULL, SA_ERR_SHAPE, SA_ERR_UNSUPPORTED, SA_ERR_WORKSPACE, SA_ERR_BAD_PERM, SA_ERR_HIP = range(7)
+SA_BF16, SA_F32 = 0, 1
+SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
+SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
+
+EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
+           "gated_sa_swa_fwd", "sa_bwd")
+
+
+class sa_desc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("n", C.c_int32),
+                ("d", C.c_int32), ("w", C.c_int32), ("window", C.c_int32),
+                ("causal_orig", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float),
+                ("perm_B", C.c_int32), ("perm_H", C.c_int32), ("gate_per_dim", C.c_int32),
+                ("gate_dtype", C.c_int32)]
+
+
+class SaError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (sa_status {status})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_00754_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz, ip = C.c_void_p, C.c_size_t, C.c_void_p
+    dp = C.POINTER(sa_desc)
+    lib.sa_status_string.restype = C.c_char_p
+    lib.sa_status_string.argtypes = [C.c_int]
+    lib.sa_workspace_bytes.restype = C.c_size_t
+    lib.sa_workspace_bytes.argtypes = [dp, C.c_int]
+    lib.sa_check_perm.restype = C.c_int
+    lib.sa_check_perm.argtypes = [dp, ip, vp, sz, vp]
+    lib.sa_fwd.restype = C.c_int
+    lib.sa_fwd.argtypes = [dp, vp, vp, vp, ip, vp, vp, vp, sz, vp]
+    lib.swa_fwd.restype = C.c_int
+    lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.gated_sa_swa_fwd.restype = C.c_int
+    lib.gated_sa_swa_fwd.argtypes = [dp, dp, vp, vp, vp, ip, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sa_bwd.restype = C.c_int
+    lib.sa_bwd.argtypes = [dp, dp] + [vp] * 17 + [sz, vp]
+    return lib
+
+
+_lib = _load()
+
+
+def status_string(status: int) -> str:
+    return _lib.sa_status_string(int(status)).decode()
+
+
+def make_desc(B, Hq, Hkv, n, d, w, window=SA_WIN_SYM_CIRCULAR, causal_orig=1, dtype=SA_BF16,
+              scale=0.0, perm_B=1, perm_H=1, gate_per_dim=0, gate_dtype=SA_F32) -> sa_desc:
+    return sa_desc(B, Hq, Hkv, n, d, w, window, causal_orig, dtype, scale, perm_B, perm_H,
+                   gate_per_dim, gate_dtype)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "libsa takes contiguous tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream) if torch.cuda.is_available() else None
+
+
+def _check(status, what):
+    if status != SA_OK:
+        raise SaError(status, what)
+
+
+def sa_workspace_bytes(desc: sa_desc, op: int) -> int:
+    return int(_lib.sa_workspace_bytes(C.byref(desc), int(op)))
+
+
+def sa_check_perm(desc, perm, ws):
+    _check(_lib.sa_check_perm(C.byref(desc), _ptr(perm), _ptr(ws), ws.numel() * ws.element_size(),
+                              _stream()), "sa_check_perm")
+
+
+def sa_fwd(desc, Q, K, V, perm, Y, LSE=None):
+    _check(_lib.sa_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(Y), _ptr(LSE),
+                       None, 0, _stream()), "sa_fwd")
+
+
+def swa_fwd(desc, Q, K, V, Y, LSE=None):
+    _check(_lib.swa_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(Y), _ptr(LSE), None, 0,
+                        _stream()), "swa_fwd")
+
+
+def gated_sa_swa_fwd(sa, swa, Q, K, V, perm, gate_sa, gate_swa, Y, Y_sa=None, Y_swa=None,
+                     LSE_sa=None, LSE_swa=None):
+    _check(_lib.gated_sa_swa_fwd(C.byref(sa), C.byref(swa), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm),
+                                 _ptr(gate_sa), _ptr(gate_swa), _ptr(Y), _ptr(Y_sa), _ptr(Y_swa),
+                                 _ptr(LSE_sa), _ptr(LSE_swa), None, 0, _stream()),
+           "gated_sa_swa_fwd")
+
+
+def sa_bwd(sa, swa, Q, K, V, perm, gate_sa, gate_swa, Y_sa, Y_swa, LSE_sa, LSE_swa, dY,
+           dQ, dK, dV, dgate_sa, dgate_swa, ws):
+    swa_ref = C.byref(swa) if swa is not None else None
+    _check(_lib.sa_bwd(C.byref(sa), swa_ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(gate_sa),
+                       _ptr(gate_swa), _ptr(Y_sa), _ptr(Y_swa), _ptr(LSE_sa), _ptr(LSE_swa),
+                       _ptr(dY), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dgate_sa), _ptr(dgate_swa),
+                       _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
+                       _stream()), "sa_bwd")
+
+
+def raw():
+    """The ctypes library handle (for host-side tests of the error paths)."""
+    return _lib

@@ -1,0 +1,257 @@
+// Host side of libsa: the extern "C" entry points declared in include/sa.h.
+// Validation happens here, before any launch; kernels live in the other files of this directory.
+#include <math.h>
+
+#include "sa_common.h"
+
+namespace {
+
+using sa::Pass;
+using sa::Window;
+
+bool desc_shape_ok(const sa_desc* c) {
+  if (c->B < 1 || c->Hq < 1 || c->Hkv < 1 || c->n < 1 || c->d < 1 || c->w < 1) return false;
+  if (c->Hq % c->Hkv != 0) return false;
+  if (c->window < SA_WIN_SYM_CIRCULAR || c->window > SA_WIN_ONE_SIDED) return false;
+  if (!(c->perm_B == 1 || c->perm_B == c->B)) return false;
+  if (!(c->perm_H == 1 || c->perm_H == c->Hq)) return false;
+  if (c->n > (1 << 30)) return false;  // slot arithmetic is done in int32 with headroom for t in (-n, 2n)
+  if ((long long)c->B * c->Hq * c->n > (1ll << 40)) return false;
+  return true;
+}
+
+sa_status validate_desc(const sa_desc* c) {
+  if (!c) return SA_ERR_NULL;
+  if (!desc_shape_ok(c)) return SA_ERR_SHAPE;
+  if (!(c->d == 64 || c->d == 128)) return SA_ERR_UNSUPPORTED;
+  if (!(c->dtype == SA_BF16 || c->dtype == SA_F32)) return SA_ERR_UNSUPPORTED;
+  if (!(c->gate_dtype == SA_BF16 || c->gate_dtype == SA_F32)) return SA_ERR_UNSUPPORTED;
+  if (!(c->gate_per_dim == 0 || c->gate_per_dim == 1)) return SA_ERR_SHAPE;
+  if (!(c->causal_orig == 0 || c->causal_orig == 1)) return SA_ERR_SHAPE;
+  if (!(c->scale == c->scale) || isinf(c->scale)) return SA_ERR_SHAPE;
+  return SA_OK;
+}
+
+// Eq. 3 / App. B window as unwrapped offsets.  "2*dist < w" on integers is dist <= (w-1)/2.
+Window make_window(const sa_desc* c) {
+  Window win;
+  const long long n = c->n, w = c->w;
+  const long long h = (w - 1) / 2;
+  if (c->window == SA_WIN_SYM_CIRCULAR) {
+    const long long hl = h < (n - 1) / 2 ? h : (n - 1) / 2;
+    const long long hr = h < n - 1 - hl ? h : n - 1 - hl;
+    win.L = (int)hl;
+    win.R = (int)hr;
+    win.circular = 1;
+  } else if (c->window == SA_WIN_SYM_LINEAR) {
+    win.L = win.R = (int)(h < n - 1 ? h : n - 1);
+    win.circular = 0;
+  } else {
+    win.L = (int)(w - 1 < n - 1 ? w - 1 : n - 1);
+    win.R = 0;
+    win.circular = 0;
+  }
+  return win;
+}
+
+Pass make_pass(const sa_desc* c, const void* Q, const void* K, const void* V, const int32_t* perm) {
+  Pass p = {};
+  p.Q = Q; p.K = K; p.V = V; p.perm = perm;
+  p.B = c->B; p.Hq = c->Hq; p.Hkv = c->Hkv; p.n = c->n; p.d = c->d; p.g = c->Hq / c->Hkv;
+  p.perm_B = perm ? c->perm_B : 1;
+  p.perm_H = perm ? c->perm_H : 1;
+  p.win = make_window(c);
+  p.causal = c->causal_orig;
+  p.scale = c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d);
+  p.hq_only = -1;
+  return p;
+}
+
+bool same_problem(const sa_desc* a, const sa_desc* b) {
+  return a->B == b->B && a->Hq == b->Hq && a->Hkv == b->Hkv && a->n == b->n && a->d == b->d &&
+         a->dtype == b->dtype && a->gate_per_dim == b->gate_per_dim && a->gate_dtype == b->gate_dtype;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct BwdWorkspace {
+  size_t off_Da, off_Db, off_dOa, off_dOb, total;
+};
+
+BwdWorkspace bwd_workspace(const sa_desc* c, bool gated) {
+  BwdWorkspace w = {};
+  const size_t rows = (size_t)c->B * c->Hq * c->n;
+  const size_t esize = c->dtype == SA_BF16 ? 2 : 4;
+  size_t off = 0;
+  w.off_Da = off; off += align256(rows * sizeof(float));
+  if (gated) {
+    w.off_Db = off; off += align256(rows * sizeof(float));
+    w.off_dOa = off; off += align256(rows * c->d * esize);
+    w.off_dOb = off; off += align256(rows * c->d * esize);
+  }
+  w.total = off;
+  return w;
+}
+
+sa_status hip_status(hipError_t e) { return e == hipSuccess ? SA_OK : (e == hipErrorNotSupported ? SA_ERR_UNSUPPORTED : SA_ERR_HIP); }
+
+hipError_t run_fwd(const sa_desc* c, const Pass& p, hipStream_t st) {
+  return c->dtype == SA_F32 ? sa::launch_fwd_rowwise_f32(p, st) : sa::launch_fwd_mfma_bf16(p, st);
+}
+
+hipError_t run_bwd(const sa_desc* c, const Pass& p, hipStream_t st) {
+  return c->dtype == SA_F32 ? sa::launch_bwd_rowwise_f32(p, st) : sa::launch_bwd_mfma_bf16(p, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sa_status_string(sa_status s) {
+  switch (s) {
+    case SA_OK: return "ok";
+    case SA_ERR_NULL: return "required pointer is NULL";
+    case SA_ERR_SHAPE: return "invalid or inconsistent sizes";
+    case SA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SA_ERR_WORKSPACE: return "workspace missing or too small";
+    case SA_ERR_BAD_PERM: return "perm is not a bijection of 0..n-1";
+    case SA_ERR_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+size_t sa_workspace_bytes(const sa_desc* c, int op) {
+  if (validate_desc(c) != SA_OK) return 0;
+  switch (op) {
+    case SA_OP_FWD:
+    case SA_OP_GATED_FWD: return 0;
+    case SA_OP_BWD: return bwd_workspace(c, false).total;
+    case SA_OP_GATED_BWD: return bwd_workspace(c, true).total;
+    case SA_OP_CHECK_PERM: return align256((size_t)c->perm_B * c->perm_H * c->n * sizeof(int)) + 256;
+    default: return 0;
+  }
+}
+
+sa_status sa_check_perm(const sa_desc* c, const int32_t* perm, void* ws, size_t ws_bytes, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!perm) return SA_ERR_NULL;
+  const size_t need = sa_workspace_bytes(c, SA_OP_CHECK_PERM);
+  if (!ws || ws_bytes < need) return SA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  int* seen = reinterpret_cast<int*>(ws);
+  int* flag = reinterpret_cast<int*>(reinterpret_cast<char*>(ws) + need - 256);
+  hipError_t e = sa::launch_check_perm(perm, c->perm_B * c->perm_H, c->n, seen, flag, st);
+  if (e != hipSuccess) return SA_ERR_HIP;
+  int host_flag = 0;
+  e = hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return SA_ERR_HIP;
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return SA_ERR_HIP;
+  return host_flag ? SA_ERR_BAD_PERM : SA_OK;
+}
+
+sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, const int32_t* perm,
+                 void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Q || !K || !V || !Y) return SA_ERR_NULL;
+  Pass p = make_pass(c, Q, K, V, perm);
+  p.Y = Y;
+  p.LSE = LSE;
+  return hip_status(run_fwd(c, p, (hipStream_t)stream));
+}
+
+sa_status swa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, void* Y, float* LSE,
+                  void* ws, size_t ws_bytes, void* stream) {
+  return sa_fwd(c, Q, K, V, nullptr, Y, LSE, ws, ws_bytes, stream);
+}
+
+sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const void* K,
+                           const void* V, const int32_t* perm, const void* gate_sa,
+                           const void* gate_swa, void* Y, void* Y_sa, void* Y_swa, float* LSE_sa,
+                           float* LSE_swa, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  sa_status s = validate_desc(sa_d);
+  if (s != SA_OK) return s;
+  s = validate_desc(swa_d);
+  if (s != SA_OK) return s;
+  if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
+  if (!Q || !K || !V || !Y || !gate_sa || !gate_swa) return SA_ERR_NULL;
+  hipStream_t st = (hipStream_t)stream;
+
+  // sliding-window branch first (Alg. 2), into Y_swa if the caller keeps it, else into Y itself
+  Pass a = make_pass(swa_d, Q, K, V, nullptr);
+  a.Y = Y_swa ? Y_swa : Y;
+  a.LSE = LSE_swa;
+  hipError_t e = run_fwd(swa_d, a, st);
+  if (e != hipSuccess) return hip_status(e);
+
+  // stochastic branch; its epilogue reads the other branch's row and forms the gated sum (Eq. 5)
+  Pass b = make_pass(sa_d, Q, K, V, perm);
+  b.Y = Y_sa;
+  b.LSE = LSE_sa;
+  b.gate_mode = 1;
+  b.gate_per_dim = sa_d->gate_per_dim;
+  b.gate_f32 = sa_d->gate_dtype == SA_F32;
+  b.gate_this = gate_sa;
+  b.gate_other = gate_swa;
+  b.Y_other = a.Y;
+  b.Yout = Y;
+  return hip_status(run_fwd(sa_d, b, st));
+}
+
+sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const void* K, const void* V,
+                 const int32_t* perm, const void* gate_sa, const void* gate_swa, const void* Y_sa,
+                 const void* Y_swa, const float* LSE_sa, const float* LSE_swa, const void* dY,
+                 void* dQ, void* dK, void* dV, void* dgate_sa, void* dgate_swa, void* ws,
+                 size_t ws_bytes, void* stream) {
+  sa_status s = validate_desc(sa_d);
+  if (s != SA_OK) return s;
+  const bool gated = swa_d != nullptr;
+  if (gated) {
+    s = validate_desc(swa_d);
+    if (s != SA_OK) return s;
+    if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
+  }
+  if (!Q || !K || !V || !Y_sa || !LSE_sa || !dY || !dQ || !dK || !dV) return SA_ERR_NULL;
+  if (gated && (!gate_sa || !gate_swa || !Y_swa || !LSE_swa || !dgate_sa || !dgate_swa)) return SA_ERR_NULL;
+  const BwdWorkspace w = bwd_workspace(sa_d, gated);
+  if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = reinterpret_cast<char*>(ws);
+
+  sa::Prep pr = {};
+  pr.rows = sa_d->B * sa_d->Hq * sa_d->n;
+  pr.d = sa_d->d;
+  pr.bf16 = sa_d->dtype == SA_BF16;
+  pr.gated = gated;
+  pr.gate_per_dim = sa_d->gate_per_dim;
+  pr.gate_f32 = sa_d->gate_dtype == SA_F32;
+  pr.dY = dY;
+  pr.Y_a = Y_sa; pr.Y_b = Y_swa;
+  pr.gate_a = gate_sa; pr.gate_b = gate_swa;
+  pr.D_a = reinterpret_cast<float*>(base + w.off_Da);
+  pr.D_b = gated ? reinterpret_cast<float*>(base + w.off_Db) : nullptr;
+  pr.dO_a = gated ? base + w.off_dOa : nullptr;
+  pr.dO_b = gated ? base + w.off_dOb : nullptr;
+  pr.dgate_a = dgate_sa; pr.dgate_b = dgate_swa;
+  hipError_t e = sa::launch_bwd_prepare(pr, st);
+  if (e != hipSuccess) return hip_status(e);
+
+  if (gated) {
+    Pass a = make_pass(swa_d, Q, K, V, nullptr);
+    a.dO = pr.dO_b; a.lse_in = LSE_swa; a.Dsum = pr.D_b;
+    a.dQ = dQ; a.dK = dK; a.dV = dV; a.accumulate = 0;
+    e = run_bwd(swa_d, a, st);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  Pass b = make_pass(sa_d, Q, K, V, perm);
+  b.dO = gated ? pr.dO_a : dY;
+  b.lse_in = LSE_sa; b.Dsum = pr.D_a;
+  b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = gated ? 1 : 0;
+  return hip_status(run_bwd(sa_d, b, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,78 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels of libsa.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sa.h"
+
+namespace sa {
+
+// Window of Eq. 3 / App. B rewritten on UNWRAPPED slot offsets: key slot t is inside the window of
+// query slot s iff -L <= t - s <= R, where for the circular kind t runs over s-L .. s+R and is
+// reduced mod n (L + R + 1 <= n, so each slot is met once), and for the other kinds 0 <= t < n.
+struct Window {
+  int L, R, circular;
+};
+
+// Everything one attention pass (forward or backward, one branch) needs.
+struct Pass {
+  const void* Q;
+  const void* K;
+  const void* V;
+  const int32_t* perm;  // nullptr = identity
+  int B, Hq, Hkv, n, d, g;
+  int perm_B, perm_H;
+  Window win;
+  int causal;
+  float scale;          // softmax scale (Eq. 1)
+  // forward outputs
+  void* Y;              // branch output rows, may be nullptr when only the gated sum is wanted
+  float* LSE;           // may be nullptr
+  // gated epilogue (Eq. 5), used by the second branch of the gated forward
+  int gate_mode;        // 0 none; 1 combine: Yout = sig(ga)*this + sig(gb)*other
+  int gate_per_dim, gate_f32;
+  const void* gate_this;
+  const void* gate_other;
+  const void* Y_other;  // the other branch's rows [B,Hq,n,d] (may alias Yout)
+  void* Yout;           // gated sum
+  // backward
+  const void* dO;       // gradient w.r.t. this branch's output [B,Hq,n,d]
+  const float* lse_in;  // [B,Hq,n]
+  const float* Dsum;    // rowsum(dO * O) [B,Hq,n]
+  void* dQ;
+  void* dK;
+  void* dV;
+  int accumulate;       // 1: add to what dQ/dK/dV already hold (second branch of the gated backward)
+  int hq_only;          // >= 0: dK/dV pass restricted to this query head of every group
+};
+
+__host__ __device__ inline int perm_slice_index(int perm_B, int perm_H, int b, int hq) {
+  return (perm_B == 1 ? 0 : b) * perm_H + (perm_H == 1 ? 0 : hq);
+}
+
+// kernels (each file checks its own launch geometry against the Pass on the host)
+hipError_t launch_fwd_rowwise_f32(const Pass& p, hipStream_t st);
+hipError_t launch_bwd_rowwise_f32(const Pass& p, hipStream_t st);
+hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st);
+hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st);
+
+// helpers in sa_misc.hip
+hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag,
+                             hipStream_t st);
+// D = rowsum(dO * O); for the gated case also dO_x = sig(gamma_x) * dY and the gate-logit gradients.
+struct Prep {
+  int rows, d;               // rows = B*Hq*n
+  int bf16;                  // dtype of Y, dY, dO
+  int gated, gate_per_dim, gate_f32;
+  const void* dY;
+  const void* Y_a;  const void* Y_b;          // branch outputs (b unused when not gated)
+  const void* gate_a; const void* gate_b;
+  void* dO_a; void* dO_b;                      // gated only
+  float* D_a; float* D_b;
+  void* dgate_a; void* dgate_b;
+};
+hipError_t launch_bwd_prepare(const Prep& p, hipStream_t st);
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);
+
+}  // namespace sa

@@ -1,0 +1,178 @@
+// Element-wise helpers of libsa: permutation check, zero fill, and the backward's preparation pass
+// (D = rowsum(dO * O), and for the gated sum of Eq. 5 the chain rule through the two sigmoid gates).
+#include "sa_common.h"
+#include "sa_device.h"
+
+namespace sa {
+namespace {
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t words) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < words; i += stride) p[i] = 0u;
+}
+
+// seen[slice][v] counts how often value v occurs in the slice; any count other than one, or a value
+// outside 0..n-1, raises the flag.
+__global__ void check_perm_kernel(const int32_t* __restrict__ perm, size_t total, int n, int* seen, int* flag) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < total; i += stride) {
+    const int v = perm[i];
+    if (v < 0 || v >= n) {
+      atomicOr(flag, 1);
+    } else if (atomicAdd(&seen[(i / n) * n + v], 1) != 0) {
+      atomicOr(flag, 1);
+    }
+  }
+}
+
+template <int LPR>  // lanes per row, each lane owns 16 bytes of the row
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// One group of LPR lanes per row; E = elements per 16-byte vector (8 bf16 / 4 f32).
+template <bool BF16, int LPR>
+__global__ __launch_bounds__(256) void bwd_prepare_kernel(Prep p) {
+  constexpr int E = BF16 ? 8 : 4;
+  const int sub = threadIdx.x % LPR;
+  const long row = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const bool valid = row < p.rows;
+  const size_t r = valid ? (size_t)row : 0;
+  const size_t off = r * p.d + (size_t)sub * E;
+
+  float dy[E], ya[E], yb[E];
+  if (BF16) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.dY) + off);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.Y_a) + off);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      dy[2 * k] = bf16lo(a[k]); dy[2 * k + 1] = bf16hi(a[k]);
+      ya[2 * k] = bf16lo(b[k]); ya[2 * k + 1] = bf16hi(b[k]);
+    }
+    if (p.gated) {
+      const u32x4 c = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.Y_b) + off);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { yb[2 * k] = bf16lo(c[k]); yb[2 * k + 1] = bf16hi(c[k]); }
+    }
+  } else {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p.dY) + off);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p.Y_a) + off);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { dy[k] = a[k]; ya[k] = b[k]; }
+    if (p.gated) {
+      const f32x4 c = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(p.Y_b) + off);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) yb[k] = c[k];
+    }
+  }
+
+  if (!p.gated) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < E; ++k) s = fmaf(dy[k], ya[k], s);
+    s = group_sum<LPR>(s);
+    if (valid && sub == 0) p.D_a[r] = s;
+    return;
+  }
+
+  // gated: dO_x = sig(gamma_x) * dY;  D_x = sum_d dO_x * Y_x;  dgamma_x = sig'(gamma_x) * dY * Y_x
+  float ga[E], gb[E];
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    const size_t gi = p.gate_per_dim ? off + k : r;
+    ga[k] = sigmoidf_exact(load_gate(p.gate_a, gi, p.gate_f32));
+    gb[k] = sigmoidf_exact(load_gate(p.gate_b, gi, p.gate_f32));
+  }
+  float da[E], db[E], sa = 0.f, sb = 0.f, ra = 0.f, rb = 0.f;
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    da[k] = ga[k] * dy[k];
+    db[k] = gb[k] * dy[k];
+    sa = fmaf(da[k], ya[k], sa);
+    sb = fmaf(db[k], yb[k], sb);
+    ra = fmaf(dy[k], ya[k], ra);
+    rb = fmaf(dy[k], yb[k], rb);
+  }
+  sa = group_sum<LPR>(sa);
+  sb = group_sum<LPR>(sb);
+  if (valid && sub == 0) {
+    p.D_a[r] = sa;
+    p.D_b[r] = sb;
+  }
+  if (p.gate_per_dim) {
+    if (valid) {
+#pragma unroll
+      for (int k = 0; k < E; ++k) {
+        store_gate(p.dgate_a, off + k, p.gate_f32, ga[k] * (1.f - ga[k]) * dy[k] * ya[k]);
+        store_gate(p.dgate_b, off + k, p.gate_f32, gb[k] * (1.f - gb[k]) * dy[k] * yb[k]);
+      }
+    }
+  } else {
+    ra = group_sum<LPR>(ra);
+    rb = group_sum<LPR>(rb);
+    if (valid && sub == 0) {
+      store_gate(p.dgate_a, r, p.gate_f32, ga[0] * (1.f - ga[0]) * ra);
+      store_gate(p.dgate_b, r, p.gate_f32, gb[0] * (1.f - gb[0]) * rb);
+    }
+  }
+  if (valid) {
+    if (BF16) {
+      u32x4 oa, ob;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        oa[k] = pack_bf16(da[2 * k], da[2 * k + 1]);
+        ob[k] = pack_bf16(db[2 * k], db[2 * k + 1]);
+      }
+      *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.dO_a) + off) = oa;
+      *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.dO_b) + off) = ob;
+    } else {
+      f32x4 oa, ob;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { oa[k] = da[k]; ob[k] = db[k]; }
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.dO_a) + off) = oa;
+      *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(p.dO_b) + off) = ob;
+    }
+  }
+}
+
+template <bool BF16, int LPR>
+hipError_t launch_prepare_t(const Prep& p, hipStream_t st) {
+  const long threads = (long)p.rows * LPR;
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  hipLaunchKernelGGL((bwd_prepare_kernel<BF16, LPR>), dim3(blocks), dim3(256), 0, st, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st) {
+  if (bytes % 4 != 0) return hipErrorInvalidValue;
+  const size_t words = bytes / 4;
+  if (words == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((words + 1023) / 1024 < 4096 ? (words + 1023) / 1024 : 4096);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint32_t*>(ptr), words);
+  return hipGetLastError();
+}
+
+hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag, hipStream_t st) {
+  const size_t total = (size_t)slices * n;
+  hipError_t e = launch_fill_zero(seen, total * sizeof(int), st);
+  if (e != hipSuccess) return e;
+  e = launch_fill_zero(flag, sizeof(int), st);
+  if (e != hipSuccess) return e;
+  const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+  hipLaunchKernelGGL(check_perm_kernel, dim3(blocks), dim3(256), 0, st, perm, total, n, seen, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_prepare(const Prep& p, hipStream_t st) {
+  if (p.rows < 1 || !(p.d == 64 || p.d == 128)) return hipErrorInvalidValue;
+  if (p.bf16) return p.d == 64 ? launch_prepare_t<true, 8>(p, st) : launch_prepare_t<true, 16>(p, st);
+  return p.d == 64 ? launch_prepare_t<false, 16>(p, st) : launch_prepare_t<false, 32>(p, st);
+}
+
+}  // namespace sa

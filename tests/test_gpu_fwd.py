@@ -1,0 +1,81 @@
+"""GPU parity of the forward entry points (sa_fwd, swa_fwd) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+CIRC, LIN, ONE = 0, 1, 2
+
+
+def run_fwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed=0, identity=False,
+            use_swa_entry=False):
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, identity=identity)
+    print(f"case fwd B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} win{window} causal{causal} {dtype} "
+          f"perm[{perm_B},{perm_H}] identity={identity}", flush=True)
+    Yr, Lr = orc.sa_fwd(U.orc_desc(wl, window, causal), x["Q"], x["K"], x["V"], x["perm"])
+    Q, K, V = (U.to_dev(x[k], dtype) for k in "QKV")
+    perm = None if identity else torch.from_numpy(x["perm"]).to(U.DEV)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    desc = U.sa_desc(wl, window, causal)
+    if use_swa_entry:
+        sa.swa_fwd(desc, Q, K, V, Y, L)
+    else:
+        sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(Y), Yr, dtype, "Y")
+    la = np.abs(U.to_np64(L) - Lr).max()
+    assert la <= (2e-3 if dtype == "bf16" else 1e-5), f"LSE max-abs {la:.3e}"
+
+
+def test_tiny_f32_config():
+    """First benchmark configuration: B=1, H=2, n=1024, d=64, w=64, fp32, one permutation per head."""
+    run_fwd(1, 2, 2, 1024, 64, 64, CIRC, 1, "f32", perm_H=2)
+
+
+@pytest.mark.parametrize("window", [CIRC, LIN, ONE])
+@pytest.mark.parametrize("causal", [0, 1])
+def test_f32_window_kinds(window, causal):
+    run_fwd(2, 4, 2, 333, 64, 37, window, causal, "f32", perm_B=2, perm_H=4, seed=1)
+
+
+def test_f32_d128_and_wide_windows():
+    run_fwd(1, 2, 1, 200, 128, 64, CIRC, 1, "f32", seed=2)
+    run_fwd(1, 2, 1, 150, 128, 151, CIRC, 1, "f32", seed=3)     # window covers the ring
+    run_fwd(1, 1, 1, 150, 64, 400, ONE, 1, "f32", seed=4, identity=True, use_swa_entry=True)
+    run_fwd(1, 1, 1, 70, 64, 1, CIRC, 1, "f32", seed=5)         # w = 1: every token sees itself only
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("window,causal", [(CIRC, 1), (CIRC, 0), (LIN, 1), (ONE, 1)])
+def test_bf16_basic(d, window, causal):
+    run_fwd(2, 4, 2, 1000, d, 128, window, causal, "bf16", perm_H=4, seed=10 + d)
+
+
+@pytest.mark.parametrize("n,w", [(77, 16), (128, 9), (129, 300), (640, 641), (1024, 1023), (300, 1), (31, 64), (513, 2)])
+def test_bf16_ragged_and_degenerate(n, w):
+    run_fwd(1, 2, 2, n, 64, w, CIRC, 1, "bf16", seed=20)
+    run_fwd(1, 2, 1, n, 128, w, CIRC, 0, "bf16", perm_H=2, seed=21)
+    run_fwd(1, 2, 1, n, 128, w, LIN, 1, "bf16", seed=22)
+
+
+def test_bf16_swa_entry_and_identity():
+    run_fwd(2, 4, 4, 900, 64, 128, ONE, 1, "bf16", identity=True, use_swa_entry=True, seed=30)
+    run_fwd(1, 4, 1, 900, 128, 100, ONE, 1, "bf16", identity=True, use_swa_entry=True, seed=31)
+    run_fwd(1, 2, 2, 900, 64, 128, CIRC, 1, "bf16", identity=True, seed=32)
+    run_fwd(1, 2, 2, 500, 64, 2000, ONE, 1, "bf16", identity=True, use_swa_entry=True, seed=33)  # full causal
+
+
+def test_bf16_gqa_shared_and_per_batch_perm():
+    run_fwd(2, 8, 2, 1100, 128, 256, CIRC, 1, "bf16", perm_B=2, perm_H=1, seed=40)
+    run_fwd(2, 8, 2, 600, 64, 256, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=41)
+
+
+def test_pretraining_shape_sample():
+    """Second benchmark configuration's shape (B=8,H=12,n=2048,d=64,w=128), SA branch only."""
+    run_fwd(8, 12, 12, 2048, 64, 128, CIRC, 1, "bf16", perm_H=12, seed=50)
