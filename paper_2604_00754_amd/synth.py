@@ -96,3 +96,16 @@ def make_inputs(wl: Workload, layer: int = 0, seed: int = 0, need=("Q", "K", "V"
             x = round_to_bf16(x)
         out[k] = x
     return out
+
+
+def sample_rows(B: int, H: int, n: int, per_head: int, seed: int) -> np.ndarray:
+    """int32 [B*H*min(per_head,n), 3] of (b, h, i): a seeded sample of rows, every head covered."""
+    g = np.random.Generator(np.random.PCG64([BASE_SEED, 2000 + seed]))
+    m = min(per_head, n)
+    out = np.empty((B, H, m, 3), np.int32)
+    for b in range(B):
+        for h in range(H):
+            out[b, h, :, 0] = b
+            out[b, h, :, 1] = h
+            out[b, h, :, 2] = np.arange(n) if m == n else np.sort(g.choice(n, size=m, replace=False))
+    return out.reshape(-1, 3)

@@ -57,8 +57,4 @@ def sa_desc(wl, window, causal, gate_per_dim=0, gate_dtype=1):
                         gate_per_dim, gate_dtype)
 
 
-def sample_rows(B, H, n, per_head, seed):
-    g = np.random.default_rng(seed)
-    rows = [(b, h, int(i)) for b in range(B) for h in range(H)
-            for i in np.sort(g.choice(n, size=min(per_head, n), replace=False))]
-    return np.array(rows, np.int32)
+sample_rows = synth.sample_rows

@@ -1,0 +1,117 @@
+"""GPU parity of sa_bwd (ungated and gated) against the fp64 oracle's analytic gradient."""
+import numpy as np
+import pytest
+import torch
+
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+CIRC, LIN, ONE = 0, 1, 2
+
+
+def grad_close(got, ref, dtype, what):
+    # max-abs bar scaled by the reference's own magnitude (gradients are not O(1) like Y)
+    U.assert_close(got, ref, dtype, what, scale_abs=max(1.0, float(np.abs(ref).max())))
+
+
+def run_bwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed=0, identity=False):
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, grads=True, identity=identity)
+    print(f"case bwd B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} win{window} causal{causal} {dtype} "
+          f"perm[{perm_B},{perm_H}] identity={identity}", flush=True)
+    oc = U.orc_desc(wl, window, causal)
+    dQr, dKr, dVr = orc.sa_bwd(oc, x["Q"], x["K"], x["V"], x["perm"], x["dY"])
+    Q, K, V, dY = (U.to_dev(x[k], dtype) for k in ("Q", "K", "V", "dY"))
+    perm = None if identity else torch.from_numpy(x["perm"]).to(U.DEV)
+    desc = U.sa_desc(wl, window, causal)
+    Y = torch.empty_like(Q)
+    L = torch.empty((B, Hq, n), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    torch.cuda.synchronize()
+    grad_close(U.to_np64(dQ), dQr, dtype, "dQ")
+    grad_close(U.to_np64(dK), dKr, dtype, "dK")
+    grad_close(U.to_np64(dV), dVr, dtype, "dV")
+
+
+def run_gated_bwd(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gate_dtype="f32", seed=0):
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, gates=True, grads=True)
+    print(f"case gated bwd B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} {dtype} perm[{perm_B},{perm_H}] "
+          f"per_dim={per_dim} gate={gate_dtype}", flush=True)
+    ga, gl = x["gate_sa"], x["gate_swa"]
+    if per_dim:
+        rng = np.random.default_rng(seed)
+        ga = rng.standard_normal((B, Hq, n, d)).astype(np.float32)
+        gl = rng.standard_normal((B, Hq, n, d)).astype(np.float32)
+    if gate_dtype == "bf16":
+        ga, gl = synth.round_to_bf16(ga), synth.round_to_bf16(gl)
+    osa, oswa = U.orc_desc(wl, CIRC, 1), U.orc_desc(wl, ONE, 1)
+    ref = orc.gated_sa_swa_bwd(osa, oswa, per_dim, x["Q"], x["K"], x["V"], x["perm"], ga, gl, x["dY"])
+    Q, K, V, dY = (U.to_dev(x[k], dtype) for k in ("Q", "K", "V", "dY"))
+    perm = torch.from_numpy(x["perm"]).to(U.DEV)
+    gdt = 1 if gate_dtype == "f32" else 0
+    tga, tgl = U.to_dev(ga, gate_dtype), U.to_dev(gl, gate_dtype)
+    dsa, dswa = U.sa_desc(wl, CIRC, 1, per_dim, gdt), U.sa_desc(wl, ONE, 1, per_dim, gdt)
+    Y, Ysa, Yswa = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    Lsa = torch.empty((B, Hq, n), device=U.DEV, dtype=torch.float32)
+    Lswa = torch.empty_like(Lsa)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa)
+    dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
+    dga, dgl = torch.full_like(tga, float("nan")), torch.full_like(tgl, float("nan"))
+    ws = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(dsa, dswa, Q, K, V, perm, tga, tgl, Ysa, Yswa, Lsa, Lswa, dY, dQ, dK, dV, dga, dgl, ws)
+    torch.cuda.synchronize()
+    for got, r, what in ((dQ, ref[0], "dQ"), (dK, ref[1], "dK"), (dV, ref[2], "dV")):
+        grad_close(U.to_np64(got), r, dtype, what)
+    gtol = "bf16" if (dtype == "bf16" or gate_dtype == "bf16") else "f32"
+    grad_close(U.to_np64(dga), ref[3], gtol, "dgate_sa")
+    grad_close(U.to_np64(dgl), ref[4], gtol, "dgate_swa")
+
+
+@pytest.mark.parametrize("window,causal", [(CIRC, 1), (CIRC, 0), (LIN, 1), (ONE, 1)])
+def test_bwd_f32(window, causal):
+    run_bwd(1, 4, 2, 300, 64, 37, window, causal, "f32", perm_H=4, seed=1)
+
+
+def test_bwd_f32_d128_and_full_ring():
+    run_bwd(1, 2, 2, 150, 128, 64, CIRC, 1, "f32", seed=2)
+    run_bwd(1, 2, 1, 90, 64, 200, CIRC, 1, "f32", seed=3)
+    run_bwd(1, 2, 2, 130, 64, 16, ONE, 1, "f32", seed=4, identity=True)
+
+
+@pytest.mark.parametrize("per_dim", [0, 1])
+def test_gated_bwd_f32(per_dim):
+    run_gated_bwd(1, 4, 2, 200, 64, 32, "f32", perm_H=4, per_dim=per_dim, seed=5)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("window,causal", [(CIRC, 1), (CIRC, 0), (LIN, 1), (ONE, 1)])
+def test_bwd_bf16(d, window, causal):
+    run_bwd(2, 4, 2, 700, d, 128, window, causal, "bf16", seed=10 + d)
+
+
+@pytest.mark.parametrize("n,w", [(77, 16), (129, 300), (640, 641), (300, 1), (31, 64), (513, 2)])
+def test_bwd_bf16_ragged_and_degenerate(n, w):
+    run_bwd(1, 2, 2, n, 64, w, CIRC, 1, "bf16", seed=20)
+    run_bwd(1, 2, 1, n, 128, w, CIRC, 0, "bf16", seed=21)
+
+
+def test_bwd_bf16_per_head_perm_with_grouped_heads():
+    run_bwd(2, 8, 2, 600, 64, 128, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=30)
+    run_bwd(1, 4, 4, 600, 64, 128, CIRC, 1, "bf16", perm_H=4, seed=31)
+
+
+@pytest.mark.parametrize("per_dim,gate_dtype", [(0, "f32"), (1, "f32"), (0, "bf16")])
+def test_gated_bwd_bf16(per_dim, gate_dtype):
+    run_gated_bwd(2, 4, 2, 700, 64, 128, "bf16", per_dim=per_dim, gate_dtype=gate_dtype, seed=40)
+
+
+def test_gated_bwd_bf16_d128():
+    run_gated_bwd(1, 4, 1, 500, 128, 96, "bf16", seed=41)

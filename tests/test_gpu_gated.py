@@ -1,0 +1,85 @@
+"""GPU parity of gated_sa_swa_fwd (Alg. 2 / Eq. 5 with gate logits as inputs) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+CIRC, LIN, ONE = 0, 1, 2
+
+
+def run_gated(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gate_dtype="f32", keep=True, seed=0,
+              saturate=None):
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, gates=True)
+    print(f"case gated B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} {dtype} perm[{perm_B},{perm_H}] per_dim={per_dim} "
+          f"gate={gate_dtype} keep={keep} saturate={saturate}", flush=True)
+    ga, gl = x["gate_sa"], x["gate_swa"]
+    if per_dim:
+        rng = np.random.default_rng(seed)
+        ga = rng.standard_normal((B, Hq, n, d)).astype(np.float32)
+        gl = rng.standard_normal((B, Hq, n, d)).astype(np.float32)
+    if gate_dtype == "bf16":
+        from paper_2604_00754_amd import synth
+        ga, gl = synth.round_to_bf16(ga), synth.round_to_bf16(gl)
+    if saturate == "sa":
+        ga, gl = np.full_like(ga, np.inf), np.full_like(gl, -np.inf)
+    if saturate == "swa":
+        ga, gl = np.full_like(ga, -np.inf), np.full_like(gl, np.inf)
+    osa, oswa = U.orc_desc(wl, CIRC, 1), U.orc_desc(wl, ONE, 1)
+    ref = orc.gated_sa_swa_fwd(osa, oswa, per_dim, x["Q"], x["K"], x["V"], x["perm"], ga, gl)
+    Q, K, V = (U.to_dev(x[k], dtype) for k in "QKV")
+    perm = torch.from_numpy(x["perm"]).to(U.DEV)
+    gdt = 1 if gate_dtype == "f32" else 0
+    tga, tgl = U.to_dev(ga, gate_dtype), U.to_dev(gl, gate_dtype)
+    Y = torch.full_like(Q, float("nan"))
+    Ysa = torch.full_like(Q, float("nan")) if keep else None
+    Yswa = torch.full_like(Q, float("nan")) if keep else None
+    Lsa = torch.full((B, Hq, n), float("nan"), device=U.DEV) if keep else None
+    Lswa = torch.full((B, Hq, n), float("nan"), device=U.DEV) if keep else None
+    dsa, dswa = U.sa_desc(wl, CIRC, 1, per_dim, gdt), U.sa_desc(wl, ONE, 1, per_dim, gdt)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(Y), ref["Y"], dtype, "Y")
+    if keep:
+        U.assert_close(U.to_np64(Ysa), ref["Ysa"], dtype, "Y_sa")
+        U.assert_close(U.to_np64(Yswa), ref["Yswa"], dtype, "Y_swa")
+        tol = 2e-3 if dtype == "bf16" else 1e-5
+        assert np.abs(U.to_np64(Lsa) - ref["LSEsa"]).max() <= tol
+        assert np.abs(U.to_np64(Lswa) - ref["LSEswa"]).max() <= tol
+    if saturate and keep:
+        # a gate at exactly 1/0 selects one branch bit for bit in the GPU's own arithmetic
+        pick = Ysa if saturate == "sa" else Yswa
+        assert torch.equal(Y, pick)
+
+
+def test_gated_f32():
+    run_gated(1, 2, 2, 300, 64, 32, "f32", perm_H=2, seed=1)
+    run_gated(1, 4, 2, 200, 128, 64, "f32", per_dim=1, keep=False, seed=2)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("per_dim", [0, 1])
+def test_gated_bf16(d, per_dim):
+    run_gated(2, 4, 2, 700, d, 128, "bf16", perm_H=4, per_dim=per_dim, seed=3)
+
+
+def test_gated_bf16_inference_mode_and_bf16_gates():
+    run_gated(1, 4, 4, 520, 64, 64, "bf16", keep=False, seed=4)
+    run_gated(1, 4, 4, 520, 64, 64, "bf16", gate_dtype="bf16", seed=5)
+    run_gated(1, 4, 1, 520, 128, 64, "bf16", gate_dtype="bf16", per_dim=1, keep=False, seed=6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("which", ["sa", "swa"])
+def test_saturated_gates_select_one_branch(dtype, which):
+    run_gated(1, 2, 2, 260, 64, 32, dtype, saturate=which, seed=7)
+
+
+def test_gated_pretraining_shape():
+    """Second benchmark configuration: B=8, H=12, n=2048, d=64, w=128, bf16, per-head permutations,
+    gate logits ~ N(0,1) per head and token."""
+    run_gated(8, 12, 12, 2048, 64, 128, "bf16", perm_H=12, seed=8)
