@@ -13,7 +13,7 @@
 // The epilogue normalises, transposes through LDS and writes each row to its ORIGINAL position
 // (the "undo permute" of Alg. 1), optionally forming the gated sum of Eq. 5 on the way out.
 #include "sa_common.h"
-#include "sa_device.h"
+#include "sa_mfma.h"
 
 namespace sa {
 namespace {
@@ -21,7 +21,6 @@ namespace {
 constexpr int BM = 128;  // query slots per workgroup
 constexpr int BN = 64;   // key slots per tile
 constexpr int NT = 256;  // threads per workgroup
-constexpr int NXCD = 8;  // workgroup ids are dealt round-robin to the 8 XCDs
 
 template <int D>
 struct Cfg {
@@ -38,18 +37,6 @@ struct Cfg {
   static_assert(QBYTES <= KBYTES + VBYTES, "staging must fit in the K|V area");
 };
 
-__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-// Transposing LDS read: within a group of 16 lanes, lane i receives element (i % 4) of the 8-byte
-// words addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group.
-__device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
-}
-
 template <int D>
 __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
   using C = Cfg<D>;
@@ -58,11 +45,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + C::KBYTES);
   int* pk_lds = reinterpret_cast<int*>(smem + C::KBYTES + C::VBYTES);
 
-  // XCD-aware work order: every XCD gets one contiguous chunk of a list in which neighbours share
-  // K/V rows (the query heads of a group, then the next query tile), so its L2 sees the reuse.
-  const long chunk = (total_work + NXCD - 1) / NXCD;
-  const long work = (long)(blockIdx.x % NXCD) * chunk + blockIdx.x / NXCD;
-  if (blockIdx.x / NXCD >= chunk || work >= total_work) return;
+  // work list order: the query heads of a group, then the next query tile -- neighbours share K/V rows
+  const long work = xcd_work_index(total_work);
+  if (work < 0) return;
   const int hg = (int)(work % p.g);
   long rest = work / p.g;
   const int qt = (int)(rest % num_qt);
@@ -251,32 +236,20 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
         pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], cs, -mc));
         l_run += pe[i];
       }
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        u32x4 w;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = pack_bf16(pe[8 * c + 2 * e], pe[8 * c + 2 * e + 1]);
-        pf[kb][c] = __builtin_bit_cast(bf16x8, w);
-      }
+      pf[kb][0] = pack_b_operand(pe);
+      pf[kb][1] = pack_b_operand(pe + 8);
     }
 
     // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts the 16 tile rows 32kb+16c+{0..3,8..11}+4*g2
     // (+4 for the second half of the lane's 8 values); the transposing read fetches exactly those.
-    const int G = lane >> 4, j16 = lane & 15;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (!act[kb]) continue;
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-          const bf16_t* base = Vs + (32 * kb + 16 * c + 4 * (G >> 1) + (j16 >> 2)) * C::VSTR + 32 * db + 16 * (G & 1) + 4 * (j16 & 3);
-          const s16x4 lo = lds_read_tr16(base);
-          const s16x4 hi = lds_read_tr16(base + 8 * C::VSTR);
-          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, a), pf[kb][c], oacc[db]);
-        }
-      }
+        for (int db = 0; db < D / 32; ++db)
+          oacc[db] = mfma_bf16(lds_read_transposed_a(Vs, C::VSTR, 32 * kb + 16 * c, 32 * db, lane), pf[kb][c], oacc[db]);
     }
   }
 
@@ -331,9 +304,9 @@ template <int D>
 hipError_t launch_t(const Pass& p, hipStream_t st) {
   const int num_qt = (p.n + BM - 1) / BM;
   const long total = (long)num_qt * p.Hq * p.B;
-  const long chunk = (total + NXCD - 1) / NXCD;
-  if (chunk * NXCD > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D>), dim3((unsigned)(chunk * NXCD)), dim3(NT), 0, st, p, num_qt, total);
+  const long blocks = xcd_grid_blocks(total);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
   return hipGetLastError();
 }
 

@@ -1,0 +1,56 @@
+// Matrix-core building blocks shared by the bf16 forward and backward kernels (gfx950).
+#pragma once
+
+#include "sa_device.h"
+
+namespace sa {
+
+constexpr int NXCD = 8;  // workgroup ids are dealt round-robin to the 8 XCDs
+
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// D = A(32x16) * B(16x32) + C.  Lane l = 32*g + r holds A[r][8g..8g+7], B[8g..8g+7][r] and the
+// accumulators C[8*(i/4) + 4g + i%4][r], i = 0..15.
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16): within a group of 16 lanes, lane i receives element
+// (i % 4) of the 8-byte words addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group.
+__device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+}
+
+// A operand X^T (32 columns of X starting at col0, contraction over 16 rows of X) for a row-major
+// LDS tile X[row][stride]: the contraction rows are row0 + {0..3, 8..11} + 4*g (lanes' first four
+// values) and +4 more (second four), which is exactly where the accumulators of a preceding
+// 32x32 product keep the values that serve as the B operand (elements 8c..8c+7 of the lane).
+__device__ __forceinline__ bf16x8 lds_read_transposed_a(const bf16_t* tile, int stride, int row0, int col0, int lane) {
+  const int G = lane >> 4, j16 = lane & 15;
+  const bf16_t* base = tile + (row0 + 4 * (G >> 1) + (j16 >> 2)) * stride + col0 + 16 * (G & 1) + 4 * (j16 & 3);
+  const s16x4 lo = lds_read_tr16(base);
+  const s16x4 hi = lds_read_tr16(base + 8 * stride);
+  const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, a);
+}
+
+// Pack accumulators 8c..8c+7 of a lane as a bf16 B operand.
+__device__ __forceinline__ bf16x8 pack_b_operand(const float* v8) {
+  u32x4 w;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = pack_bf16(v8[2 * e], v8[2 * e + 1]);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// XCD-aware work index: every XCD gets one contiguous chunk of the work list, so that neighbours
+// in the list (which share K/V or Q/dO rows) meet in the same L2.  Returns -1 for surplus blocks.
+__device__ __forceinline__ long xcd_work_index(long total_work) {
+  const long chunk = (total_work + NXCD - 1) / NXCD;
+  const long local = blockIdx.x / NXCD;
+  const long work = (long)(blockIdx.x % NXCD) * chunk + local;
+  return (local >= chunk || work >= total_work) ? -1 : work;
+}
+
+inline long xcd_grid_blocks(long total_work) { return (total_work + NXCD - 1) / NXCD * NXCD; }
+
+}  // namespace sa

@@ -30,10 +30,15 @@ def errors(got: np.ndarray, ref: np.ndarray):
 
 
 def assert_close(got, ref, dtype, what, scale_abs=1.0):
+    """max-abs and relative-L2 bars of the benchmark definition.  When the reference is (numerically)
+    the zero tensor -- e.g. the gradient w.r.t. Q and K when every query sees a single key -- a
+    relative error has no meaning and only the max-abs bar is applied."""
     ma, rl = errors(got, ref)
     amax, rmax = TOL[dtype]
     assert np.isfinite(got).all(), f"{what}: non-finite values"
-    assert ma <= amax * scale_abs and rl <= rmax, f"{what}: max-abs {ma:.3e} (<= {amax * scale_abs:.1e}) rel-L2 {rl:.3e} (<= {rmax:.1e})"
+    ref_rms = float(np.sqrt(np.mean(ref.astype(np.float64) ** 2)))
+    rel_ok = rl <= rmax or ref_rms < 1e-4
+    assert ma <= amax * scale_abs and rel_ok, f"{what}: max-abs {ma:.3e} (<= {amax * scale_abs:.1e}) rel-L2 {rl:.3e} (<= {rmax:.1e})"
     return ma, rl
 
 
