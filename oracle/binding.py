@@ -160,3 +160,19 @@ def sa_bwd_dkv_rows(c, Q, K, V, perm, dY, rows):
                                      C.c_int64(rows.shape[0]), _p(dK), _p(dV)),
            "orc_sa_bwd_dkv_rows")
     return dK, dV
+
+
+def gate_bwd(c, per_dim, dY, gsa, gswa, Ysa=None, Yswa=None):
+    """Returns (dYsa, dYswa) or, when Ysa/Yswa are given, (dYsa, dYswa, dgsa, dgswa)."""
+    qs, gs = (c.B, c.Hq, c.n, c.d), _gate_shape(c, per_dim)
+    dY, gsa, gswa = _f64(dY, qs), _f64(gsa, gs), _f64(gswa, gs)
+    da, dl = np.empty(qs, np.float64), np.empty(qs, np.float64)
+    if Ysa is None:
+        _check(lib().orc_gate_bwd(C.byref(c), int(per_dim), _p(dY), _p(gsa), _p(gswa), None, None,
+                                  _p(da), _p(dl), None, None), "orc_gate_bwd")
+        return da, dl
+    Ysa, Yswa = _f64(Ysa, qs), _f64(Yswa, qs)
+    dga, dgl = np.empty(gs, np.float64), np.empty(gs, np.float64)
+    _check(lib().orc_gate_bwd(C.byref(c), int(per_dim), _p(dY), _p(gsa), _p(gswa), _p(Ysa), _p(Yswa),
+                              _p(da), _p(dl), _p(dga), _p(dgl)), "orc_gate_bwd")
+    return da, dl, dga, dgl

@@ -408,9 +408,47 @@ int orc_sa_bwd(const orc_desc* c, const double* Q, const double* K, const double
   return 0;
 }
 
-/* Chain rule through Eq. 5: with a = sig(gamma_sa), l = sig(gamma_swa),
+/* Chain rule through Eq. 5, element-wise: with a = sig(gamma_sa), l = sig(gamma_swa),
  *   dY_sa = a * dY,  dgamma_sa = a(1-a) * dY*Y_sa  (summed over d when the gate is per token),
- * likewise for the sliding-window branch; dQ, dK, dV are the sums over both branches. */
+ * likewise for the sliding-window branch.  Rows are independent, so the tensors may also be any
+ * subset of rows presented as [B,Hq,n,d] with matching logits.  Ysa, Yswa, dgsa, dgswa may all be
+ * NULL when only dY_sa / dY_swa are wanted. */
+int orc_gate_bwd(const orc_desc* c, int gate_per_dim, const double* dY,
+                 const double* gsa, const double* gswa, const double* Ysa, const double* Yswa,
+                 double* dYsa, double* dYswa, double* dgsa, double* dgswa) {
+  if (!desc_ok(c) || !dY || !gsa || !gswa || !dYsa || !dYswa) return -1;
+  const int want_dg = dgsa || dgswa;
+  if (want_dg && (!dgsa || !dgswa || !Ysa || !Yswa)) return -1;
+  const int64_t rows = (int64_t)c->B * c->Hq * c->n;
+  const int d = c->d;
+  for (int64_t r = 0; r < rows; ++r) {
+    double acc_a = 0.0, acc_l = 0.0;
+    for (int k = 0; k < d; ++k) {
+      int64_t e = r * d + k;
+      double a = sigmoid(gate_per_dim ? gsa[e] : gsa[r]);
+      double l = sigmoid(gate_per_dim ? gswa[e] : gswa[r]);
+      dYsa[e] = a * dY[e];
+      dYswa[e] = l * dY[e];
+      if (!want_dg) continue;
+      if (gate_per_dim) {
+        dgsa[e] = a * (1.0 - a) * dY[e] * Ysa[e];
+        dgswa[e] = l * (1.0 - l) * dY[e] * Yswa[e];
+      } else {
+        acc_a += dY[e] * Ysa[e];
+        acc_l += dY[e] * Yswa[e];
+      }
+    }
+    if (want_dg && !gate_per_dim) {
+      double a = sigmoid(gsa[r]), l = sigmoid(gswa[r]);
+      dgsa[r] = a * (1.0 - a) * acc_a;
+      dgswa[r] = l * (1.0 - l) * acc_l;
+    }
+  }
+  return 0;
+}
+
+/* Gradient of Alg. 2 (with the gate logits as inputs): both branches forward, Eq. 5's chain rule,
+ * each branch's attention gradient, and the sum of the two for dQ, dK, dV. */
 int orc_gated_sa_swa_bwd(const orc_desc* sa, const orc_desc* swa, int gate_per_dim,
                          const double* Q, const double* K, const double* V,
                          const int32_t* perm, const double* gsa, const double* gswa,
@@ -419,9 +457,7 @@ int orc_gated_sa_swa_bwd(const orc_desc* sa, const orc_desc* swa, int gate_per_d
                          double* dgsa, double* dgswa) {
   if (!desc_ok(sa) || !desc_ok(swa) || !same_shape(sa, swa)) return -1;
   if (!gsa || !gswa || !dY || !dQ || !dK || !dV || !dgsa || !dgswa) return -1;
-  const int64_t rows = (int64_t)sa->B * sa->Hq * sa->n;
-  const int d = sa->d;
-  const size_t nq = (size_t)rows * d, nk = (size_t)sa->B * sa->Hkv * sa->n * d;
+  const size_t nq = (size_t)sa->B * sa->Hq * sa->n * sa->d, nk = (size_t)sa->B * sa->Hkv * sa->n * sa->d;
   double* ya = (double*)malloc(sizeof(double) * nq);
   double* yl = (double*)malloc(sizeof(double) * nq);
   double* da = (double*)malloc(sizeof(double) * nq);
@@ -432,35 +468,12 @@ int orc_gated_sa_swa_bwd(const orc_desc* sa, const orc_desc* swa, int gate_per_d
   if (!ya || !yl || !da || !dl || !dQ2 || !dK2 || !dV2) return -3;
   int rc = orc_sa_fwd(sa, Q, K, V, perm, ya, NULL);
   if (!rc) rc = orc_sa_fwd(swa, Q, K, V, NULL, yl, NULL);
+  if (!rc) rc = orc_gate_bwd(sa, gate_per_dim, dY, gsa, gswa, ya, yl, da, dl, dgsa, dgswa);
+  if (!rc) rc = orc_sa_bwd(sa, Q, K, V, perm, da, dQ, dK, dV);
+  if (!rc) rc = orc_sa_bwd(swa, Q, K, V, NULL, dl, dQ2, dK2, dV2);
   if (!rc) {
-    for (int64_t r = 0; r < rows; ++r) {
-      double acc_a = 0.0, acc_l = 0.0;
-      for (int k = 0; k < d; ++k) {
-        int64_t e = r * d + k;
-        double a = sigmoid(gate_per_dim ? gsa[e] : gsa[r]);
-        double l = sigmoid(gate_per_dim ? gswa[e] : gswa[r]);
-        da[e] = a * dY[e];
-        dl[e] = l * dY[e];
-        if (gate_per_dim) {
-          dgsa[e] = a * (1.0 - a) * dY[e] * ya[e];
-          dgswa[e] = l * (1.0 - l) * dY[e] * yl[e];
-        } else {
-          acc_a += dY[e] * ya[e];
-          acc_l += dY[e] * yl[e];
-        }
-      }
-      if (!gate_per_dim) {
-        double a = sigmoid(gsa[r]), l = sigmoid(gswa[r]);
-        dgsa[r] = a * (1.0 - a) * acc_a;
-        dgswa[r] = l * (1.0 - l) * acc_l;
-      }
-    }
-    rc = orc_sa_bwd(sa, Q, K, V, perm, da, dQ, dK, dV);
-    if (!rc) rc = orc_sa_bwd(swa, Q, K, V, NULL, dl, dQ2, dK2, dV2);
-    if (!rc) {
-      for (size_t e = 0; e < nq; ++e) dQ[e] += dQ2[e];
-      for (size_t e = 0; e < nk; ++e) { dK[e] += dK2[e]; dV[e] += dV2[e]; }
-    }
+    for (size_t e = 0; e < nq; ++e) dQ[e] += dQ2[e];
+    for (size_t e = 0; e < nk; ++e) { dK[e] += dK2[e]; dV[e] += dV2[e]; }
   }
   free(ya); free(yl); free(da); free(dl); free(dQ2); free(dK2); free(dV2);
   return rc;

@@ -88,6 +88,13 @@ int orc_gated_sa_swa_bwd(const orc_desc* sa, const orc_desc* swa, int gate_per_d
                          double* dQ, double* dK, double* dV,
                          double* dgsa, double* dgswa);
 
+/* Chain rule through Eq. 5 alone (element-wise): dYsa = sig(gsa)*dY, dYswa = sig(gswa)*dY and, when
+ * dgsa/dgswa/Ysa/Yswa are given, the gate-logit gradients.  Works on any set of rows presented as
+ * [B,Hq,n,d]. */
+int orc_gate_bwd(const orc_desc* c, int gate_per_dim, const double* dY,
+                 const double* gsa, const double* gswa, const double* Ysa, const double* Yswa,
+                 double* dYsa, double* dYswa, double* dgsa, double* dgswa);
+
 /* Row-sampled gradients for sizes where the full backward is too slow.
  * dQ rows: rows[3*r..] = (b,hq,i) -> dQ_rows [nrows,d].
  * dK/dV rows: rows[3*r..] = (b,hk,j) -> dK_rows, dV_rows [nrows,d]

@@ -1,0 +1,116 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol include/sa.h declares, and
+reports argument errors before anything is launched (no GPU needed, no kernel is run)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_00754_amd import binding as sa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(4096)  # never dereferenced: every call below must fail validation first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:sa|swa|gated)_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert set(names) == set(sa.EXPORTS), names
+    lib = sa.raw()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    for code in range(7):
+        assert sa.status_string(code) and sa.status_string(code) != "unknown status"
+    assert sa.status_string(99) == "unknown status"
+
+
+def good():
+    return sa.make_desc(2, 8, 2, 1000, 128, 256, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+
+
+def fwd(desc, q=FAKE, k=FAKE, v=FAKE, y=FAKE):
+    d = C.byref(desc) if desc is not None else None
+    return sa.raw().sa_fwd(d, q, k, v, None, y, None, None, 0, None)
+
+
+def test_null_arguments():
+    assert fwd(None) == sa.SA_ERR_NULL
+    for kw in ("q", "k", "v", "y"):
+        assert fwd(good(), **{kw: None}) == sa.SA_ERR_NULL
+    d = good()
+    assert sa.raw().sa_check_perm(C.byref(d), None, FAKE, 1 << 30, None) == sa.SA_ERR_NULL
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("B", 0, sa.SA_ERR_SHAPE), ("n", 0, sa.SA_ERR_SHAPE), ("w", 0, sa.SA_ERR_SHAPE),
+    ("Hkv", 3, sa.SA_ERR_SHAPE), ("window", 3, sa.SA_ERR_SHAPE), ("window", -1, sa.SA_ERR_SHAPE),
+    ("perm_B", 3, sa.SA_ERR_SHAPE), ("perm_H", 2, sa.SA_ERR_SHAPE), ("causal_orig", 2, sa.SA_ERR_SHAPE),
+    ("gate_per_dim", 2, sa.SA_ERR_SHAPE), ("scale", float("nan"), sa.SA_ERR_SHAPE),
+    ("d", 96, sa.SA_ERR_UNSUPPORTED), ("d", 256, sa.SA_ERR_UNSUPPORTED), ("dtype", 2, sa.SA_ERR_UNSUPPORTED),
+    ("gate_dtype", 5, sa.SA_ERR_UNSUPPORTED),
+])
+def test_bad_descriptors(field, value, status):
+    d = good()
+    setattr(d, field, value)
+    assert fwd(d) == status
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_BWD) == 0
+
+
+def test_workspace_sizes_and_checks():
+    d = good()
+    rows = d.B * d.Hq * d.n
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_FWD) == 0
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_GATED_FWD) == 0
+    ws_bwd = sa.sa_workspace_bytes(d, sa.SA_OP_BWD)
+    ws_gated = sa.sa_workspace_bytes(d, sa.SA_OP_GATED_BWD)
+    assert ws_bwd >= rows * 4 and ws_bwd % 256 == 0
+    assert ws_gated >= 2 * rows * 4 + 2 * rows * d.d * 2
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_CHECK_PERM) >= d.n * 4 + 4
+    lib = sa.raw()
+    args = [C.byref(d), None] + [FAKE] * 17
+    # ungated backward: workspace too small / missing
+    assert lib.sa_bwd(*args, ws_bwd - 1, None) == sa.SA_ERR_WORKSPACE
+    args_nows = list(args)
+    args_nows[18] = None
+    assert lib.sa_bwd(*args_nows, ws_bwd, None) == sa.SA_ERR_WORKSPACE
+    # gated backward needs the larger workspace and all gate pointers
+    swa = good()
+    swa.window = sa.SA_WIN_ONE_SIDED
+    gargs = [C.byref(d), C.byref(swa)] + [FAKE] * 17
+    assert lib.sa_bwd(*gargs, ws_bwd, None) == sa.SA_ERR_WORKSPACE
+    gargs_null = list(gargs)
+    gargs_null[6] = None  # gate_sa
+    assert lib.sa_bwd(*gargs_null, ws_gated, None) == sa.SA_ERR_NULL
+    assert lib.sa_check_perm(C.byref(d), FAKE, FAKE, 16, None) == sa.SA_ERR_WORKSPACE
+
+
+def test_gated_descriptors_must_agree():
+    a, b = good(), good()
+    b.window = sa.SA_WIN_ONE_SIDED
+    lib = sa.raw()
+    call = lambda x, y: lib.gated_sa_swa_fwd(C.byref(x), C.byref(y), FAKE, FAKE, FAKE, None, FAKE, FAKE,
+                                             FAKE, None, None, None, None, None, 0, None)
+    b.n = 999
+    assert call(a, b) == sa.SA_ERR_SHAPE
+    b.n = a.n
+    b.dtype = sa.SA_F32
+    assert call(a, b) == sa.SA_ERR_SHAPE
+    b.dtype = a.dtype
+    assert lib.gated_sa_swa_fwd(C.byref(a), C.byref(b), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None,
+                                None, None, None, None, 0, None) == sa.SA_ERR_NULL
+
+
+def test_binding_raises_with_status():
+    d = good()
+    d.d = 96
+    with pytest.raises(sa.SaError) as e:
+        sa._check(fwd(d), "sa_fwd")
+    assert e.value.status == sa.SA_ERR_UNSUPPORTED
