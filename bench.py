@@ -71,6 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--cpu-rows-per-head", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-step", action="store_true", help="time the step only (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -116,12 +117,14 @@ def main():
     roofline_hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": gbs / PEAK_HBM_GBS, "algorithmic_bytes": alg_bytes}
 
-    # the same call with the identity permutation and the one-sided causal window (plain SWA)
-    swa_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16,
-                            0.0, 1, 1)
-    Y2 = torch.empty_like(Q)
-    _, swa_ms = time_op(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
-    other = {"swa_fwd_ms": swa_ms, "swa_fwd_tokens_per_s": wl.B * wl.n / (swa_ms * 1e-3)}
+    other = {}
+    if not args.only_step:
+        # the same call with the identity permutation and the one-sided causal window (plain SWA)
+        swa_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16,
+                                0.0, 1, 1)
+        Y2 = torch.empty_like(Q)
+        _, swa_ms = time_op(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
+        other = {"swa_fwd_ms": swa_ms, "swa_fwd_tokens_per_s": wl.B * wl.n / (swa_ms * 1e-3)}
 
     out = {"metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -133,7 +136,7 @@ def main():
            "tflops_band": tflops, "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
            "roofline": roofline, "roofline_hbm": roofline_hbm, "other_ops": other}
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.only_step:
         base, rows, Yr = cpu_baseline(wl, Q, K, V, perm, args.cpu_rows_per_head)
         ri = torch.from_numpy(rows.astype(np.int64)).to(dev)
         got = Y[ri[:, 0], ri[:, 1], ri[:, 2]].float().cpu().numpy().astype(np.float64)

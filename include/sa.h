@@ -96,7 +96,9 @@ sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void*
 /* Alg. 2 / Eq. 5 with the gate logits as inputs.  `sa` and `swa` describe the masks of the two
  * branches and must agree in every other field.  gate_sa / gate_swa: logits, [B,Hq,n] or
  * [B,Hq,n,d] per sa->gate_per_dim, of sa->gate_dtype.
- * Y_sa, Y_swa (branch outputs, needed by the backward), LSE_sa, LSE_swa may each be NULL. */
+ * Y_sa, Y_swa (branch outputs, needed by the backward), LSE_sa, LSE_swa may each be NULL.
+ * ws: sa_workspace_bytes(sa, SA_OP_GATED_FWD) bytes (bf16: the first branch is kept in fp32 there so
+ * that the gated sum is rounded once; fp32: none needed). */
 sa_status gated_sa_swa_fwd(const sa_desc* sa, const sa_desc* swa,
                            const void* Q, const void* K, const void* V, const int32_t* perm,
                            const void* gate_sa, const void* gate_swa,

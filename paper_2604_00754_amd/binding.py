@@ -107,10 +107,11 @@ def swa_fwd(desc, Q, K, V, Y, LSE=None):
 
 
 def gated_sa_swa_fwd(sa, swa, Q, K, V, perm, gate_sa, gate_swa, Y, Y_sa=None, Y_swa=None,
-                     LSE_sa=None, LSE_swa=None):
+                     LSE_sa=None, LSE_swa=None, ws=None):
     _check(_lib.gated_sa_swa_fwd(C.byref(sa), C.byref(swa), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm),
                                  _ptr(gate_sa), _ptr(gate_swa), _ptr(Y), _ptr(Y_sa), _ptr(Y_swa),
-                                 _ptr(LSE_sa), _ptr(LSE_swa), None, 0, _stream()),
+                                 _ptr(LSE_sa), _ptr(LSE_swa), _ptr(ws),
+                                 (ws.numel() * ws.element_size()) if ws is not None else 0, _stream()),
            "gated_sa_swa_fwd")
 
 

@@ -93,6 +93,12 @@ BwdWorkspace bwd_workspace(const sa_desc* c, bool gated) {
   return w;
 }
 
+// The bf16 gated forward keeps the first branch's rows in fp32 until the gated sum is rounded.
+size_t gated_fwd_workspace(const sa_desc* c) {
+  if (c->dtype != SA_BF16) return 0;
+  return align256((size_t)c->B * c->Hq * c->n * c->d * sizeof(float));
+}
+
 sa_status hip_status(hipError_t e) { return e == hipSuccess ? SA_OK : (e == hipErrorNotSupported ? SA_ERR_UNSUPPORTED : SA_ERR_HIP); }
 
 hipError_t run_fwd(const sa_desc* c, const Pass& p, hipStream_t st) {
@@ -123,8 +129,8 @@ const char* sa_status_string(sa_status s) {
 size_t sa_workspace_bytes(const sa_desc* c, int op) {
   if (validate_desc(c) != SA_OK) return 0;
   switch (op) {
-    case SA_OP_FWD:
-    case SA_OP_GATED_FWD: return 0;
+    case SA_OP_FWD: return 0;
+    case SA_OP_GATED_FWD: return gated_fwd_workspace(c);
     case SA_OP_BWD: return bwd_workspace(c, false).total;
     case SA_OP_GATED_BWD: return bwd_workspace(c, true).total;
     case SA_OP_CHECK_PERM: return align256((size_t)c->perm_B * c->perm_H * c->n * sizeof(int)) + 256;
@@ -172,18 +178,22 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
                            const void* V, const int32_t* perm, const void* gate_sa,
                            const void* gate_swa, void* Y, void* Y_sa, void* Y_swa, float* LSE_sa,
                            float* LSE_swa, void* ws, size_t ws_bytes, void* stream) {
-  (void)ws; (void)ws_bytes;
   sa_status s = validate_desc(sa_d);
   if (s != SA_OK) return s;
   s = validate_desc(swa_d);
   if (s != SA_OK) return s;
   if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
   if (!Q || !K || !V || !Y || !gate_sa || !gate_swa) return SA_ERR_NULL;
+  const size_t need = gated_fwd_workspace(sa_d);
+  if (need && (!ws || ws_bytes < need)) return SA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  const bool bf16 = sa_d->dtype == SA_BF16;
 
-  // sliding-window branch first (Alg. 2), into Y_swa if the caller keeps it, else into Y itself
+  // sliding-window branch first (Alg. 2).  bf16: rows also go to the workspace in fp32 (and to Y_swa
+  // if the caller keeps it); fp32: rows go to Y_swa, or to Y itself when Y_swa is not wanted.
   Pass a = make_pass(swa_d, Q, K, V, nullptr);
-  a.Y = Y_swa ? Y_swa : Y;
+  a.Y = bf16 ? Y_swa : (Y_swa ? Y_swa : Y);
+  a.Y_f32_out = bf16 ? reinterpret_cast<float*>(ws) : nullptr;
   a.LSE = LSE_swa;
   hipError_t e = run_fwd(swa_d, a, st);
   if (e != hipSuccess) return hip_status(e);
@@ -197,7 +207,8 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   b.gate_f32 = sa_d->gate_dtype == SA_F32;
   b.gate_this = gate_sa;
   b.gate_other = gate_swa;
-  b.Y_other = a.Y;
+  b.Y_other = bf16 ? nullptr : a.Y;
+  b.Y_other_f32 = bf16 ? reinterpret_cast<const float*>(ws) : nullptr;
   b.Yout = Y;
   return hip_status(run_fwd(sa_d, b, st));
 }

@@ -3,15 +3,19 @@
 // One workgroup (4 wavefronts) owns 128 consecutive PERMUTED slots of one (batch, query head); a
 // wavefront owns 32 of them.  The workgroup walks the slots of the window band (Eq. 3) in tiles of
 // 64; K and V rows of a tile are read through the index tensor straight from their original
-// positions (the permuted copies of Alg. 1 never exist), staged in LDS, and consumed by
+// positions (the permuted copies of Alg. 1 never exist), staged in LDS (double buffered, one
+// barrier per tile), and consumed by
 //   S^T = K Q^T          (v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in registers)
 //   mask: window on slot offsets, causal test on original positions (Sec. 3.3, App. B)
 //   online softmax (Eq. 1) -- in the S^T layout a lane holds one query column, so row statistics
-//   are lane-local up to one exchange with lane^32
-//   O^T += V^T P^T       (A = V read from LDS with the transposing ds_read_b64_tr_b16, B = P^T
-//                         taken directly from the S^T accumulators)
+//   are lane-local up to one exchange with lane^32; the running maximum is only moved when a tile
+//   exceeds it by more than 2^8, which leaves the normalised result unchanged
+//   O^T += V^T P^T       (A = V^T from LDS, stored transposed by the loader so that the reads are
+//                         plain 16-byte ones; B = P^T taken directly from the S^T accumulators)
 // The epilogue normalises, transposes through LDS and writes each row to its ORIGINAL position
 // (the "undo permute" of Alg. 1), optionally forming the gated sum of Eq. 5 on the way out.
+#include <type_traits>
+
 #include "sa_common.h"
 #include "sa_mfma.h"
 
@@ -24,26 +28,36 @@ constexpr int NT = 256;  // threads per workgroup
 
 template <int D>
 struct Cfg {
-  static constexpr int KSTR = D + 8;    // bf16 per K row in LDS: +16 B keeps 16 consecutive rows on distinct banks for b128 reads
-  static constexpr int VSTR = D + 32;   // bf16 per V row in LDS: +64 B spreads 4 consecutive rows over the 4 bank quadrants for the transposing read
-  static constexpr int VPR = D / 8;     // 16-byte vectors per row
-  static constexpr int RPP = NT / VPR;  // tile rows covered by one pass of the workgroup
-  static constexpr int NV = BN / RPP;   // vectors per thread per tile (per tensor)
-  static constexpr int WRPP = 64 / VPR; // rows covered by one pass of a single wave
+  static constexpr int KSTR = D + 8;     // bf16 per K row in LDS: +16 B keeps 16 consecutive rows on distinct banks for 16-byte reads
+  static constexpr int VTSTR = BN + 8;   // bf16 per V^T row (one d, 64 key slots) in LDS, same padding rule
+  static constexpr int VPR = D / 8;      // 16-byte vectors per K/V row
+  static constexpr int RPP = NT / VPR;   // K rows covered by one pass of the workgroup
+  static constexpr int NV = BN / RPP;    // K vectors per thread per tile
+  static constexpr int VUNITS = 16 * VPR;  // V work units: (group of 4 key rows) x (16-byte chunk)
+  static constexpr int WRPP = 64 / VPR;  // rows covered by one pass of a single wave
   static constexpr int KBYTES = BN * KSTR * 2;
-  static constexpr int VBYTES = BN * VSTR * 2;
-  static constexpr int QBYTES = 4 * 32 * KSTR * 2;  // per-wave Q / O staging, aliases K|V
-  static constexpr int LDS_BYTES = KBYTES + VBYTES + BN * 4;
-  static_assert(QBYTES <= KBYTES + VBYTES, "staging must fit in the K|V area");
+  static constexpr int VBYTES = D * VTSTR * 2;
+  static constexpr int BUF_BYTES = KBYTES + VBYTES;  // K | V^T
+  static constexpr int QBYTES = 4 * 32 * KSTR * 2;   // per-wave Q / O staging, aliases one buffer
+  static constexpr int RING = 4;                     // tiles whose row indices are kept in LDS
+  static constexpr int LDS_BYTES = 2 * BUF_BYTES + RING * BN * 4;
+  static_assert(QBYTES <= BUF_BYTES, "staging must fit in one buffer");
+  static_assert(VUNITS <= NT, "one V unit per thread at most");
+  static_assert(BUF_BYTES % 16 == 0, "buffers stay 16-byte aligned");
 };
 
-template <int D>
+// Position of key row k (0..63) inside a V^T row.  Accumulator i = 8c + 4h + x of lane group g holds
+// tile row 32kb + 16c + 8h + 4g + x; storing it at 32kb + 16c + 8g + 4h + x makes the 8 values a
+// lane needs for MFMA step (kb, c) one contiguous 16-byte read.
+__device__ __forceinline__ int vt_pos4(int u) {  // u = k / 4 -> position / 4
+  return (u & 12) | ((u & 1) << 1) | ((u & 2) >> 1);
+}
+
+// PERM = false: identity permutation (plain windowed attention); no index loads are generated.
+template <int D, bool PERM>
 __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + C::KBYTES);
-  int* pk_lds = reinterpret_cast<int*>(smem + C::KBYTES + C::VBYTES);
 
   // work list order: the query heads of a group, then the next query tile -- neighbours share K/V rows
   const long work = xcd_work_index(total_work);
@@ -56,12 +70,14 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const int b = (int)(rest / p.Hkv);
   const int hq = hk * p.g + hg;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
   const bool circular = p.win.circular != 0, causal = p.causal != 0;
   const int32_t* __restrict__ perm =
-      p.perm ? p.perm + (size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * n : nullptr;
+      PERM ? p.perm + (size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * n : nullptr;
+  auto orig_of = [&](int slot) -> int { return PERM ? perm[slot] : slot; };
   const bf16_t* __restrict__ Qh = reinterpret_cast<const bf16_t*>(p.Q) + ((size_t)b * p.Hq + hq) * n * (size_t)D;
   const bf16_t* __restrict__ Kh = reinterpret_cast<const bf16_t*>(p.K) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   const bf16_t* __restrict__ Vh = reinterpret_cast<const bf16_t*>(p.V) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
@@ -70,7 +86,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const int q_last = min(p0 + BM - 1, n - 1);
   const int s_w0 = p0 + 32 * wave;  // first query slot of this wave
   const int s = s_w0 + c32;         // this lane's query slot (column of S^T)
-  const int orig_q = slot_to_orig(perm, min(s, n - 1));
+  const int orig_q = orig_of(min(s, n - 1));
 
   // key-slot range of the workgroup, unwrapped
   int t_lo = p0 - L, t_hi = q_last + R;
@@ -80,17 +96,35 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   }
   const int ntiles = (t_hi - t_lo + BN) / BN;
 
-  // ---- stage this wave's 32 query rows through LDS and keep them as B operands
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::KSTR;
+  // ---- original indices of the rows of tiles 0..2 go to the LDS ring; tile 3's stay in a register
+  int* ring = reinterpret_cast<int*>(smem + 2 * C::BUF_BYTES);
+  auto tile_row_orig = [&](int tile) -> int {  // original index of row `tid` of a tile (clamped to the range)
+    return orig_of(wrap_slot(min(t_lo + tile * BN + tid, t_hi), n));
+  };
+  int pk_reg = 0;
+  if (tid < BN) {
+    const int i0 = tile_row_orig(0), i1 = tile_row_orig(1), i2 = tile_row_orig(2);
+    pk_reg = tile_row_orig(3);
+    ring[0 * BN + tid] = i0;
+    ring[1 * BN + tid] = i1;
+    ring[2 * BN + tid] = i2;
+  }
+
+  // ---- stage this wave's 32 query rows through LDS (second buffer) and keep them as B operands
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::KSTR;
   {
+    constexpr int NP = 32 / C::WRPP;
     const int chunk16 = lane % C::VPR;
+    int src[NP];
+    u32x4 v[NP];
 #pragma unroll
-    for (int pass = 0; pass < 32 / C::WRPP; ++pass) {
-      const int row = pass * C::WRPP + lane / C::VPR;
-      const int src = slot_to_orig(perm, min(s_w0 + row, n - 1));
-      const u32x4 v = *reinterpret_cast<const u32x4*>(Qh + (size_t)src * D + chunk16 * 8);
-      *reinterpret_cast<u32x4*>(Qs + row * C::KSTR + chunk16 * 8) = v;
-    }
+    for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass)
+      v[pass] = *reinterpret_cast<const u32x4*>(Qh + (size_t)src[pass] * D + chunk16 * 8);
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass)
+      *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::VPR) * C::KSTR + chunk16 * 8) = v[pass];
   }
   __syncthreads();
   bf16x8 qf[D / 16];
@@ -98,32 +132,53 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   for (int kk = 0; kk < D / 16; ++kk)
     qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::KSTR + 16 * kk + 8 * g2);
 
-  // ---- tile loader: thread -> rows (v*RPP + tid/VPR), 16-byte chunk tid%VPR
+  // ---- tile loader.  K: thread -> rows (v*RPP + tid/VPR), 16-byte chunk tid%VPR, stored row-major.
+  // V: thread -> 4 consecutive rows 4u..4u+3 (u = tid%16) and chunk tid/16, transposed in registers
+  // and stored as V^T (8 rows of 4 key slots each).  Row indices come from the LDS ring.
   const int ld_row = tid / C::VPR, ld_chunk = tid % C::VPR;
-  int idx[C::NV];  // original indices of this thread's rows of the tile being fetched next
-  int pk_next = 0; // original index of tile row `tid` (threads < BN), for the causal test
-  auto load_idx = [&](int tile) {
-    const int t0 = t_lo + tile * BN;
+  const int vu = tid & 15, vdc = tid >> 4;
+  const bool v_thread = tid < C::VUNITS;
+  u32x4 kreg[C::NV], vreg[4];
+  auto load_rows = [&](int tile) {
+    const int* idx = ring + (tile & (C::RING - 1)) * BN;
+    int kidx[C::NV];
 #pragma unroll
-    for (int v = 0; v < C::NV; ++v) {
-      const int t = min(t0 + v * C::RPP + ld_row, t_hi);
-      idx[v] = slot_to_orig(perm, wrap_slot(t, n));
+    for (int v = 0; v < C::NV; ++v) kidx[v] = idx[v * C::RPP + ld_row];
+    const int4 vidx = *reinterpret_cast<const int4*>(idx + 4 * vu);
+#pragma unroll
+    for (int v = 0; v < C::NV; ++v)
+      kreg[v] = *reinterpret_cast<const u32x4*>(Kh + (size_t)kidx[v] * D + ld_chunk * 8);
+    if (v_thread) {
+      vreg[0] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.x * D + vdc * 8);
+      vreg[1] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.y * D + vdc * 8);
+      vreg[2] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.z * D + vdc * 8);
+      vreg[3] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.w * D + vdc * 8);
     }
-    if (tid < BN) pk_next = slot_to_orig(perm, wrap_slot(min(t0 + tid, t_hi), n));
   };
-  u32x4 kreg[C::NV], vreg[C::NV];
-  auto load_rows = [&]() {
+  auto store_tile = [&](int buf) {
+    bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + buf * C::BUF_BYTES);
+    bf16_t* Vt = reinterpret_cast<bf16_t*>(smem + buf * C::BUF_BYTES + C::KBYTES);
 #pragma unroll
-    for (int v = 0; v < C::NV; ++v) {
-      kreg[v] = *reinterpret_cast<const u32x4*>(Kh + (size_t)idx[v] * D + ld_chunk * 8);
-      vreg[v] = *reinterpret_cast<const u32x4*>(Vh + (size_t)idx[v] * D + ld_chunk * 8);
+    for (int v = 0; v < C::NV; ++v)
+      *reinterpret_cast<u32x4*>(Ks + (v * C::RPP + ld_row) * C::KSTR + ld_chunk * 8) = kreg[v];
+    if (v_thread) {
+      bf16_t* dst = Vt + (8 * vdc) * C::VTSTR + 4 * vt_pos4(vu);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {  // dword m of each row holds d = 8*vdc + 2m, 2m+1
+        u32x2 lo, hi;
+        lo[0] = __builtin_amdgcn_perm(vreg[1][m], vreg[0][m], 0x05040100u);
+        lo[1] = __builtin_amdgcn_perm(vreg[3][m], vreg[2][m], 0x05040100u);
+        hi[0] = __builtin_amdgcn_perm(vreg[1][m], vreg[0][m], 0x07060302u);
+        hi[1] = __builtin_amdgcn_perm(vreg[3][m], vreg[2][m], 0x07060302u);
+        *reinterpret_cast<u32x2*>(dst + (2 * m) * C::VTSTR) = lo;
+        *reinterpret_cast<u32x2*>(dst + (2 * m + 1) * C::VTSTR) = hi;
+      }
     }
   };
 
-  load_idx(0);
-  load_rows();
-  int pk_cur = pk_next;
-  if (ntiles > 1) load_idx(1);
+  load_rows(0);
+  store_tile(0);  // buffer 0 is not the Q staging area
+  if (ntiles > 1) load_rows(1);
 
   // ---- per-lane window constants: key t is visible iff 0 <= t - s + Ll <= LRl (unsigned compare)
   const int Ll = circular ? L : min(L, max(s, 0));
@@ -131,28 +186,30 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const unsigned LRl = (unsigned)(Ll + Rl);
 
   const float cs = p.scale * kLog2e;  // exp(scale*x) = exp2(cs*x)
-  float m_run = -INFINITY, l_run = 0.f;
+  const float lazy = 8.0f / cs;       // move the reference maximum only for jumps above 2^8
+  float m_ref = -INFINITY, l_run = 0.f;
   f32x16 oacc[D / 32];
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
 
-  for (int tile = 0; tile < ntiles; ++tile) {
-    __syncthreads();  // everyone is done reading the previous tile (and the Q staging)
-#pragma unroll
-    for (int v = 0; v < C::NV; ++v) {
-      const int row = v * C::RPP + ld_row;
-      *reinterpret_cast<u32x4*>(Ks + row * C::KSTR + ld_chunk * 8) = kreg[v];
-      *reinterpret_cast<u32x4*>(Vs + row * C::VSTR + ld_chunk * 8) = vreg[v];
-    }
-    if (tid < BN) pk_lds[tid] = pk_cur;
+  // one tile; BUF (0/1) is a compile-time constant so that all LDS addresses are immediates
+  auto do_tile = [&](const int tile, auto bufc) {
+    constexpr int buf = decltype(bufc)::value;
+    // tile's buffer is complete and visible; everyone is done with the other buffer (tile-1, Q staging)
     __syncthreads();
-    if (tile + 1 < ntiles) {  // fetch the next tile while this one is consumed
-      load_rows();
-      pk_cur = pk_next;
-      if (tile + 2 < ntiles) load_idx(tile + 2);
+    if (tid < BN) {  // indices: tile+3 -> ring, tile+4 -> register
+      ring[((tile + 3) & (C::RING - 1)) * BN + tid] = pk_reg;
+      if (tile + 4 < ntiles) pk_reg = tile_row_orig(tile + 4);
     }
+    if (tile + 1 < ntiles) {
+      store_tile(buf ^ 1);
+      if (tile + 2 < ntiles) load_rows(tile + 2);
+    }
+    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES);
+    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES + C::KBYTES);
+    const int* pk_lds = ring + (tile & (C::RING - 1)) * BN;
 
     const int t0 = t_lo + tile * BN;
     bool act[2], inside[2];
@@ -163,7 +220,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       act[kb] = !(dmax < -L || dmin > R) && tb0 <= t_hi;
       inside[kb] = dmin >= -L && dmax <= R && tb0 + 31 <= t_hi && s_w0 + 31 <= q_last;
     }
-    if (!act[0] && !act[1]) continue;
+    if (!act[0] && !act[1]) return;
 
     // ---- S^T = K Q^T for the active 32-slot blocks
     f32x16 sacc[2];
@@ -207,25 +264,25 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       }
     }
 
-    // ---- online softmax (Eq. 1) on the lane's query column
+    // ---- online softmax (Eq. 1) on the lane's query column, with a lazily updated reference maximum:
+    // p = exp2(cs*(s - m_ref)) stays <= 2^8, and O and l carry the same reference, so O/l is unchanged
     float mx = sacc[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    if (__any(m_new > m_run)) {
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * cs);
+    if (__any(mx > m_ref + lazy)) {  // (-inf + lazy = -inf: the first visible key always triggers)
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = (mx > m_ref + lazy) ? __builtin_amdgcn_exp2f((m_ref - m_new) * cs) : 1.f;
+      if (mx > m_ref + lazy) m_ref = m_new;
       l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     }
-    m_run = m_new;
-    const float mc = m_safe * cs;
+    const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * cs;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
@@ -240,63 +297,101 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       pf[kb][1] = pack_b_operand(pe + 8);
     }
 
-    // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts the 16 tile rows 32kb+16c+{0..3,8..11}+4*g2
-    // (+4 for the second half of the lane's 8 values); the transposing read fetches exactly those.
+    // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts tile rows 32kb+16c+{0..3,8..11}+4*g2 (+4 for the
+    // second half of the lane's 8 values); V^T rows keep exactly those 8 slots contiguous.
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (!act[kb]) continue;
 #pragma unroll
       for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-          oacc[db] = mfma_bf16(lds_read_transposed_a(Vs, C::VSTR, 32 * kb + 16 * c, 32 * db, lane), pf[kb][c], oacc[db]);
+        for (int db = 0; db < D / 32; ++db) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (32 * db + c32) * C::VTSTR + 32 * kb + 16 * c + 8 * g2);
+          oacc[db] = mfma_bf16(a, pf[kb][c], oacc[db]);
+        }
     }
+  };
+  for (int tile = 0; tile < ntiles; tile += 2) {
+    do_tile(tile, std::integral_constant<int, 0>{});
+    if (tile + 1 < ntiles) do_tile(tile + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- epilogue: normalise, transpose through LDS, scatter rows to their original positions
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv_l = 1.f / l_tot;
-  __syncthreads();  // all waves are done with the last tile before the staging area is reused
-  bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::KSTR;
+  const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
+  const size_t my_row = head_row0 + orig_q;  // this lane's output row (valid when s < n)
+  if (p.LSE && g2 == 0 && s < n) p.LSE[my_row] = m_ref * p.scale + __logf(l_tot);
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int mq = 0; mq < 4; ++mq) {
-      u32x2 w;
-      w[0] = pack_bf16(oacc[db][4 * mq + 0] * inv_l, oacc[db][4 * mq + 1] * inv_l);
-      w[1] = pack_bf16(oacc[db][4 * mq + 2] * inv_l, oacc[db][4 * mq + 3] * inv_l);
-      *reinterpret_cast<u32x2*>(Os + c32 * C::KSTR + 32 * db + 8 * mq + 4 * g2) = w;
-    }
-  const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
-  if (p.LSE && g2 == 0 && s < n) p.LSE[head_row0 + orig_q] = m_run * p.scale + __logf(l_tot);
-  __syncthreads();
-  {
+    for (int i = 0; i < 16; ++i) oacc[db][i] *= inv_l;
+
+  // accumulator (db, 4mq..4mq+3) of a lane = elements 32db + 8mq + 4g2 .. +3 of its row
+  if (p.Y_f32_out && s < n) {  // first branch of the gated forward: keep an unrounded copy
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        const f32x4 v = {oacc[db][4 * mq], oacc[db][4 * mq + 1], oacc[db][4 * mq + 2], oacc[db][4 * mq + 3]};
+        *reinterpret_cast<f32x4*>(p.Y_f32_out + my_row * D + 32 * db + 8 * mq + 4 * g2) = v;
+      }
+  }
+
+  bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::KSTR;
+  auto stage_and_store = [&](const f32x16* acc, void* dst_tensor) {
+    __syncthreads();  // the staging area is free (last tile consumed / previous staging pass stored)
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[db][4 * mq + 0], acc[db][4 * mq + 1]);
+        w[1] = pack_bf16(acc[db][4 * mq + 2], acc[db][4 * mq + 3]);
+        *reinterpret_cast<u32x2*>(Os + c32 * C::KSTR + 32 * db + 8 * mq + 4 * g2) = w;
+      }
+    __syncthreads();
+    constexpr int NP = 32 / C::WRPP;
     const int chunk16 = lane % C::VPR;
+    int dst[NP];
 #pragma unroll
-    for (int pass = 0; pass < 32 / C::WRPP; ++pass) {
+    for (int pass = 0; pass < NP; ++pass) dst[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass) {
       const int row = pass * C::WRPP + lane / C::VPR;
-      if (s_w0 + row >= n) continue;
-      const size_t orow = head_row0 + slot_to_orig(perm, s_w0 + row);
-      const u32x4 y = *reinterpret_cast<const u32x4*>(Os + row * C::KSTR + chunk16 * 8);
-      const size_t eoff = orow * D + chunk16 * 8;
-      if (p.Y) *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.Y) + eoff) = y;
-      if (p.gate_mode) {
-        // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other
-        const u32x4 o = *reinterpret_cast<const u32x4*>(reinterpret_cast<const bf16_t*>(p.Y_other) + eoff);
-        u32x4 r;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const size_t g0 = p.gate_per_dim ? eoff + 2 * e : orow;
-          const size_t g1 = p.gate_per_dim ? eoff + 2 * e + 1 : orow;
-          const float ga0 = sigmoidf_exact(load_gate(p.gate_this, g0, p.gate_f32));
-          const float ga1 = sigmoidf_exact(load_gate(p.gate_this, g1, p.gate_f32));
-          const float gb0 = sigmoidf_exact(load_gate(p.gate_other, g0, p.gate_f32));
-          const float gb1 = sigmoidf_exact(load_gate(p.gate_other, g1, p.gate_f32));
-          r[e] = pack_bf16(ga0 * bf16lo(y[e]) + gb0 * bf16lo(o[e]), ga1 * bf16hi(y[e]) + gb1 * bf16hi(o[e]));
-        }
-        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.Yout) + eoff) = r;
+      if (s_w0 + row < n) {
+        const size_t eoff = (head_row0 + dst[pass]) * D + chunk16 * 8;
+        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(dst_tensor) + eoff) =
+            *reinterpret_cast<const u32x4*>(Os + row * C::KSTR + chunk16 * 8);
       }
     }
+  };
+
+  if (p.Y) stage_and_store(oacc, p.Y);
+  if (p.gate_mode) {
+    // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other, formed in fp32 and rounded once
+    const size_t r = s < n ? my_row : head_row0;
+    float ga = 0.f, gb = 0.f;
+    if (!p.gate_per_dim) {
+      ga = sigmoidf_exact(load_gate(p.gate_this, r, p.gate_f32));
+      gb = sigmoidf_exact(load_gate(p.gate_other, r, p.gate_f32));
+    }
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        const size_t e0 = r * D + 32 * db + 8 * mq + 4 * g2;
+        const f32x4 o = *reinterpret_cast<const f32x4*>(p.Y_other_f32 + e0);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          if (p.gate_per_dim) {
+            ga = sigmoidf_exact(load_gate(p.gate_this, e0 + x, p.gate_f32));
+            gb = sigmoidf_exact(load_gate(p.gate_other, e0 + x, p.gate_f32));
+          }
+          oacc[db][4 * mq + x] = ga * oacc[db][4 * mq + x] + gb * o[x];
+        }
+      }
+    stage_and_store(oacc, p.Yout);
   }
 }
 
@@ -306,7 +401,11 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
   const long total = (long)num_qt * p.Hq * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+  if (p.perm) {
+    hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, true>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+  } else {
+    hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, false>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+  }
   return hipGetLastError();
 }
 
@@ -317,7 +416,7 @@ hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (p.n < 1 || p.B < 1 || p.Hq < 1 || p.Hkv < 1 || p.g * p.Hkv != p.Hq) return hipErrorInvalidValue;
   if (p.win.L < 0 || p.win.R < 0 || p.win.L >= p.n || p.win.R >= p.n) return hipErrorInvalidValue;
   if (p.win.circular && p.win.L + p.win.R + 1 > p.n) return hipErrorInvalidValue;
-  if (p.gate_mode && (!p.gate_this || !p.gate_other || !p.Y_other || !p.Yout)) return hipErrorInvalidValue;
+  if (p.gate_mode && (!p.gate_this || !p.gate_other || !p.Y_other_f32 || !p.Yout)) return hipErrorInvalidValue;
   if (p.d == 64) return launch_t<64>(p, st);
   if (p.d == 128) return launch_t<128>(p, st);
   return hipErrorNotSupported;

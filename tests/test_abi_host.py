@@ -68,7 +68,10 @@ def test_workspace_sizes_and_checks():
     d = good()
     rows = d.B * d.Hq * d.n
     assert sa.sa_workspace_bytes(d, sa.SA_OP_FWD) == 0
-    assert sa.sa_workspace_bytes(d, sa.SA_OP_GATED_FWD) == 0
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_GATED_FWD) >= rows * d.d * 4
+    f32 = good()
+    f32.dtype = sa.SA_F32
+    assert sa.sa_workspace_bytes(f32, sa.SA_OP_GATED_FWD) == 0
     ws_bwd = sa.sa_workspace_bytes(d, sa.SA_OP_BWD)
     ws_gated = sa.sa_workspace_bytes(d, sa.SA_OP_GATED_BWD)
     assert ws_bwd >= rows * 4 and ws_bwd % 256 == 0
@@ -104,6 +107,7 @@ def test_gated_descriptors_must_agree():
     b.dtype = sa.SA_F32
     assert call(a, b) == sa.SA_ERR_SHAPE
     b.dtype = a.dtype
+    assert call(a, b) == sa.SA_ERR_WORKSPACE
     assert lib.gated_sa_swa_fwd(C.byref(a), C.byref(b), FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None,
                                 None, None, None, None, 0, None) == sa.SA_ERR_NULL
 

@@ -62,7 +62,8 @@ def run_gated_bwd(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gat
     Y, Ysa, Yswa = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
     Lsa = torch.empty((B, Hq, n), device=U.DEV, dtype=torch.float32)
     Lswa = torch.empty_like(Lsa)
-    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa)
+    wsf = torch.empty(max(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), 16), device=U.DEV, dtype=torch.uint8)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
     dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
     dga, dgl = torch.full_like(tga, float("nan")), torch.full_like(tgl, float("nan"))
     ws = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=U.DEV, dtype=torch.uint8)

@@ -87,7 +87,8 @@ def test_pretrain_fwdbwd_8k_gated_sampled_rows():
     Y, Ysa, Yswa = (torch.full_like(Q, float("nan")) for _ in range(3))
     Lsa = torch.empty((B, H, n), device=U.DEV, dtype=torch.float32)
     Lswa = torch.empty_like(Lsa)
-    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa)
+    wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=U.DEV, dtype=torch.uint8)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
     dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
     dga, dgl = torch.full_like(ga, float("nan")), torch.full_like(gl, float("nan"))
     ws = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=U.DEV, dtype=torch.uint8)

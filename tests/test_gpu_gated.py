@@ -41,7 +41,8 @@ def run_gated(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gate_dt
     Lsa = torch.full((B, Hq, n), float("nan"), device=U.DEV) if keep else None
     Lswa = torch.full((B, Hq, n), float("nan"), device=U.DEV) if keep else None
     dsa, dswa = U.sa_desc(wl, CIRC, 1, per_dim, gdt), U.sa_desc(wl, ONE, 1, per_dim, gdt)
-    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa)
+    wsf = torch.empty(max(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), 16), device=U.DEV, dtype=torch.uint8)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
     torch.cuda.synchronize()
     U.assert_close(U.to_np64(Y), ref["Y"], dtype, "Y")
     if keep:
