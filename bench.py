@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 METRIC = "SA fwd(+bwd) tokens/s and TFLOP/s (% bf16 MFMA peak) at n=32K, w=512"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per sa_fwd launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE scaled
+# by 2.000, WRITE_SIZE by 1.000 against a 1 GiB copy); see profiles/fwd_mfma_bf16_d128_qwen3_8b_prefill_32k.md
+MEASURED_TRAFFIC_BYTES = 397352 * 1024 + 302841 * 1024
 
 
 def band_slots(n, w, window):
@@ -64,6 +67,42 @@ def cpu_baseline(wl, Q, K, V, perm, rows_per_head):
                       f"({rows.shape[0]} rows, {dt:.1f} s)"}, rows, Y
 
 
+def training_ops(sa, synth, dev, reps):
+    """Side measurements (not the headline): the pre-training shapes, forward and backward.
+    B=4, H=16, n=8192, d=64, w=256: ungated SA fwd+bwd and gated SA+SWA fwd+bwd."""
+    wl = synth.WORKLOADS["pretrain_fwdbwd_8k"]
+    B, H, n, d, w = wl.B, wl.Hq, wl.n, wl.d, wl.w
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.BASE_SEED + 1)
+    rn = lambda shape, dt=torch.bfloat16: torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(dt)
+    Q, K, V, dY = (rn((B, H, n, d)) for _ in range(4))
+    ga, gl = rn((B, H, n), torch.float32), rn((B, H, n), torch.float32)
+    perm = torch.from_numpy(synth.permutations(1, 1, n)).to(dev)
+    dsa = sa.make_desc(B, H, H, n, d, w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+    dswa = sa.make_desc(B, H, H, n, d, w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
+    Y, Ysa, Yswa, dQ, dK, dV = (torch.empty_like(Q) for _ in range(6))
+    Lsa = torch.empty((B, H, n), device=dev, dtype=torch.float32)
+    Lswa, dga, dgl = torch.empty_like(Lsa), torch.empty_like(ga), torch.empty_like(gl)
+    wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=dev, dtype=torch.uint8)
+    wsb = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=dev, dtype=torch.uint8)
+    _, t_fwd = time_op(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Ysa, Lsa), reps, 2)
+    _, t_bwd = time_op(lambda: sa.sa_bwd(dsa, None, Q, K, V, perm, None, None, Ysa, None, Lsa, None, dY,
+                                         dQ, dK, dV, None, None, wsb), reps, 2)
+    _, t_gfwd = time_op(lambda: sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa,
+                                                    wsf), reps, 2)
+    _, t_gbwd = time_op(lambda: sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY,
+                                          dQ, dK, dV, dga, dgl, wsb), reps, 2)
+    W = band_slots(n, w, 0)
+    flop_fb = 14.0 * n * W * d * B * H  # forward 4, backward 10 per (query, in-window slot, d)
+    return {"pretrain_8k": {
+        "shape": "B4 H16 n8192 d64 w256 bf16",
+        "sa_fwd_ms": t_fwd, "sa_bwd_ms": t_bwd,
+        "sa_fwdbwd_tokens_per_s": B * n / ((t_fwd + t_bwd) * 1e-3),
+        "sa_fwdbwd_band_tflops": flop_fb / ((t_fwd + t_bwd) * 1e-3) / 1e12,
+        "gated_fwd_ms": t_gfwd, "gated_bwd_ms": t_gbwd,
+        "gated_fwdbwd_tokens_per_s": B * n / ((t_gfwd + t_gbwd) * 1e-3)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +111,9 @@ def main():
     ap.add_argument("--cpu-rows-per-head", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-step", action="store_true", help="time the step only (for profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy before and between steps (a known-size kernel "
+                         "for scaling the FETCH_SIZE / WRITE_SIZE counters; it also empties the caches)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -97,7 +139,14 @@ def main():
     desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16,
                         0.0, 1, 1)
 
+    copy_src = copy_dst = None
+    if args.calibrate_copy:
+        copy_src = torch.zeros(256 * 1024 * 1024, device=dev, dtype=torch.float32)  # 1 GiB
+        copy_dst = torch.empty_like(copy_src)
+
     def step():
+        if copy_src is not None:
+            copy_dst.copy_(copy_src)
         sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
 
     wall, launch_ms = time_op(step, args.steps, args.warmup)
@@ -112,7 +161,7 @@ def main():
     tflops = band_flop / (launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128>", "achieved": tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                "traffic": None, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms}
+                "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms}
     gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
     roofline_hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": gbs / PEAK_HBM_GBS, "algorithmic_bytes": alg_bytes}
@@ -125,6 +174,8 @@ def main():
         Y2 = torch.empty_like(Q)
         _, swa_ms = time_op(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
         other = {"swa_fwd_ms": swa_ms, "swa_fwd_tokens_per_s": wl.B * wl.n / (swa_ms * 1e-3)}
+        del Y2
+        other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
 
     out = {"metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
