@@ -42,6 +42,30 @@ __device__ __forceinline__ bf16x8 pack_b_operand(const float* v8) {
   return __builtin_bit_cast(bf16x8, w);
 }
 
+// Position (in units of 4 slots) of the 4-slot group u of a streamed tile inside a row of its
+// transposed LDS copy.  Accumulator i = 8c + 4h + x of lane group g holds tile row
+// 32kb + 16c + 8h + 4g + x; storing that row at 32kb + 16c + 8g + 4h + x makes the 8 values a lane
+// needs as A operand of MFMA step (kb, c) one contiguous 16-byte read.
+__device__ __forceinline__ int transposed_pos4(int u) {
+  return (u & ~3) | ((u & 1) << 1) | ((u & 2) >> 1);
+}
+
+// r[j] = 16 bytes (8 bf16: columns 8*dc .. 8*dc+7) of tile row 4u+j, j = 0..3.  Writes the 4x8
+// transpose: for each of the 8 columns the 4 consecutive rows as one 8-byte word of the
+// transposed tile Xt[column][slot position] (row stride tstr elements); dst = Xt + 8*dc*tstr + 4*pos4(u).
+__device__ __forceinline__ void store_transposed_4x8(bf16_t* dst, int tstr, const u32x4* r) {
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {  // dword m of each row holds columns 2m, 2m+1
+    u32x2 lo, hi;
+    lo[0] = __builtin_amdgcn_perm(r[1][m], r[0][m], 0x05040100u);
+    lo[1] = __builtin_amdgcn_perm(r[3][m], r[2][m], 0x05040100u);
+    hi[0] = __builtin_amdgcn_perm(r[1][m], r[0][m], 0x07060302u);
+    hi[1] = __builtin_amdgcn_perm(r[3][m], r[2][m], 0x07060302u);
+    *reinterpret_cast<u32x2*>(dst + (2 * m) * tstr) = lo;
+    *reinterpret_cast<u32x2*>(dst + (2 * m + 1) * tstr) = hi;
+  }
+}
+
 // XCD-aware work index: every XCD gets one contiguous chunk of the work list, so that neighbours
 // in the list (which share K/V or Q/dO rows) meet in the same L2.  Returns -1 for surplus blocks.
 __device__ __forceinline__ long xcd_work_index(long total_work) {

@@ -79,3 +79,20 @@ def test_bf16_gqa_shared_and_per_batch_perm():
 def test_pretraining_shape_sample():
     """Second benchmark configuration's shape (B=8,H=12,n=2048,d=64,w=128), SA branch only."""
     run_fwd(8, 12, 12, 2048, 64, 128, CIRC, 1, "bf16", perm_H=12, seed=50)
+
+
+def test_check_perm_accepts_bijections_and_rejects_others():
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    B, H, n = 2, 3, 1000
+    desc = sa.make_desc(B, H, H, n, 64, 32, perm_B=B, perm_H=H)
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_CHECK_PERM), device=U.DEV, dtype=torch.uint8)
+    good = torch.from_numpy(synth.permutations(B, H, n)).to(U.DEV)
+    sa.sa_check_perm(desc, good, ws)
+    sa.sa_check_perm(desc, good, ws)  # the workspace is cleared by the call itself
+    for bad_value in (good[0, 0, 5].item(), -1, n):
+        bad = good.clone()
+        bad[1, 2, 7] = bad_value if bad_value != good[1, 2, 7].item() else good[1, 2, 8].item()
+        with pytest.raises(sa.SaError) as e:
+            sa.sa_check_perm(desc, bad, ws)
+        assert e.value.status == sa.SA_ERR_BAD_PERM
