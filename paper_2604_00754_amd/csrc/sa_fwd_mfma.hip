@@ -40,7 +40,7 @@ struct Cfg {
   static constexpr int BUF_BYTES = KBYTES + VBYTES;  // K | V^T
   static constexpr int QBYTES = 4 * 32 * KSTR * 2;   // per-wave Q / O staging, aliases one buffer
   static constexpr int RING = 4;                     // tiles whose row indices are kept in LDS
-  static constexpr int LDS_BYTES = 2 * BUF_BYTES + RING * BN * 4;
+  static constexpr int LDS_BYTES = 2 * BUF_BYTES + RING * BN * 6 + BM * 4;  // buffers | index ring | 16-bit index ring | row stash
   static_assert(QBYTES <= BUF_BYTES, "staging must fit in one buffer");
   static_assert(VUNITS <= NT, "one V unit per thread at most");
   static_assert(BUF_BYTES % 16 == 0, "buffers stay 16-byte aligned");
@@ -53,8 +53,21 @@ __device__ __forceinline__ int vt_pos4(int u) {  // u = k / 4 -> position / 4
   return (u & 12) | ((u & 1) << 1) | ((u & 2) >> 1);
 }
 
+// 16-byte chunk `chunk` of row `row` of a [n, D] bf16 head: a 32-bit byte offset from the (wave-uniform)
+// head pointer, so the address needs one vector instruction (the host checks n * D * 2 < 2^31).
+template <int D>
+__device__ __forceinline__ u32x4 load_row_chunk(const bf16_t* head, int row, int chunk) {
+  const uint32_t off = (uint32_t)row * (uint32_t)(D * 2) + (uint32_t)chunk * 16u;
+  return *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(head) + off);
+}
+
+// Causal test modes.  CAUSAL_NONE: no test.  CAUSAL_I32: scores of later keys are set to -inf before
+// the softmax (any n).  CAUSAL_I16 (n <= 65535): the probabilities of later keys are cleared after
+// they are packed to bf16 pairs, with packed 16-bit compares on biased original indices.
+enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
+
 // PERM = false: identity permutation (plain windowed attention); no index loads are generated.
-template <int D, bool PERM>
+template <int D, bool PERM, int CAUSAL>
 __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
@@ -74,7 +87,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
-  const bool circular = p.win.circular != 0, causal = p.causal != 0;
+  const bool circular = p.win.circular != 0;
   const int32_t* __restrict__ perm =
       PERM ? p.perm + (size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * n : nullptr;
   auto orig_of = [&](int slot) -> int { return PERM ? perm[slot] : slot; };
@@ -101,6 +114,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   auto tile_row_orig = [&](int tile) -> int {  // original index of row `tid` of a tile (clamped to the range)
     return orig_of(wrap_slot(min(t_lo + tile * BN + tid, t_hi), n));
   };
+  // CAUSAL_I16 keeps a second copy for the mask: index - 32768 as int16, ordered so that a lane's 16
+  // accumulators of a block (key rows 8*(i/4) + 4*g2 + i%4) are 32 contiguous bytes
+  short* ring16 = reinterpret_cast<short*>(smem + 2 * C::BUF_BYTES + C::RING * BN * 4);
+  const int pos16 = (tid & 32) | ((tid & 4) << 2) | ((tid >> 1) & 12) | (tid & 3);  // row tid -> (kb, g2, i)
+  // ---- prologue.  All index loads first (this lane's query, the wave's query rows, the rows of tiles
+  // 0..3); then, one memory round trip later, the Q rows and the K/V rows of tile 0 together.
+  constexpr int NP = 32 / C::WRPP;
+  const int chunk16 = lane % C::VPR;
+  int src[NP];
+#pragma unroll
+  for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
+  int* rowstash = reinterpret_cast<int*>(smem + 2 * C::BUF_BYTES + C::RING * BN * 6);  // original index of the workgroup's 128 rows
   int pk_reg = 0;
   if (tid < BN) {
     const int i0 = tile_row_orig(0), i1 = tile_row_orig(1), i2 = tile_row_orig(2);
@@ -108,29 +133,17 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     ring[0 * BN + tid] = i0;
     ring[1 * BN + tid] = i1;
     ring[2 * BN + tid] = i2;
+    if (CAUSAL == CAUSAL_I16) {
+      ring16[0 * BN + pos16] = (short)(i0 - 32768);
+      ring16[1 * BN + pos16] = (short)(i1 - 32768);
+      ring16[2 * BN + pos16] = (short)(i2 - 32768);
+    }
   }
-
-  // ---- stage this wave's 32 query rows through LDS (second buffer) and keep them as B operands
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::KSTR;
-  {
-    constexpr int NP = 32 / C::WRPP;
-    const int chunk16 = lane % C::VPR;
-    int src[NP];
-    u32x4 v[NP];
+  if (chunk16 == 0) {
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
-#pragma unroll
-    for (int pass = 0; pass < NP; ++pass)
-      v[pass] = *reinterpret_cast<const u32x4*>(Qh + (size_t)src[pass] * D + chunk16 * 8);
-#pragma unroll
-    for (int pass = 0; pass < NP; ++pass)
-      *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::VPR) * C::KSTR + chunk16 * 8) = v[pass];
+    for (int pass = 0; pass < NP; ++pass) rowstash[wave * 32 + pass * C::WRPP + lane / C::VPR] = src[pass];
   }
-  __syncthreads();
-  bf16x8 qf[D / 16];
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk)
-    qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::KSTR + 16 * kk + 8 * g2);
+  __syncthreads();  // ring visible
 
   // ---- tile loader.  K: thread -> rows (v*RPP + tid/VPR), 16-byte chunk tid%VPR, stored row-major.
   // V: thread -> 4 consecutive rows 4u..4u+3 (u = tid%16) and chunk tid/16, transposed in registers
@@ -147,12 +160,12 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     const int4 vidx = *reinterpret_cast<const int4*>(idx + 4 * vu);
 #pragma unroll
     for (int v = 0; v < C::NV; ++v)
-      kreg[v] = *reinterpret_cast<const u32x4*>(Kh + (size_t)kidx[v] * D + ld_chunk * 8);
+      kreg[v] = load_row_chunk<D>(Kh, kidx[v], ld_chunk);
     if (v_thread) {
-      vreg[0] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.x * D + vdc * 8);
-      vreg[1] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.y * D + vdc * 8);
-      vreg[2] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.z * D + vdc * 8);
-      vreg[3] = *reinterpret_cast<const u32x4*>(Vh + (size_t)vidx.w * D + vdc * 8);
+      vreg[0] = load_row_chunk<D>(Vh, vidx.x, vdc);
+      vreg[1] = load_row_chunk<D>(Vh, vidx.y, vdc);
+      vreg[2] = load_row_chunk<D>(Vh, vidx.z, vdc);
+      vreg[3] = load_row_chunk<D>(Vh, vidx.w, vdc);
     }
   };
   auto store_tile = [&](int buf) {
@@ -176,9 +189,25 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     }
   };
 
-  load_rows(0);
+  // ---- this wave's 32 query rows go through LDS (second buffer) and are kept as B operands
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::KSTR;
+  {
+    u32x4 v[NP];
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass) v[pass] = load_row_chunk<D>(Qh, src[pass], chunk16);
+    load_rows(0);
+#pragma unroll
+    for (int pass = 0; pass < NP; ++pass)
+      *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::VPR) * C::KSTR + chunk16 * 8) = v[pass];
+  }
   store_tile(0);  // buffer 0 is not the Q staging area
   if (ntiles > 1) load_rows(1);
+  __syncthreads();
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk)
+    qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::KSTR + 16 * kk + 8 * g2);
+
 
   // ---- per-lane window constants: key t is visible iff 0 <= t - s + Ll <= LRl (unsigned compare)
   const int Ll = circular ? L : min(L, max(s, 0));
@@ -201,6 +230,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     __syncthreads();
     if (tid < BN) {  // indices: tile+3 -> ring, tile+4 -> register
       ring[((tile + 3) & (C::RING - 1)) * BN + tid] = pk_reg;
+      if (CAUSAL == CAUSAL_I16) ring16[((tile + 3) & (C::RING - 1)) * BN + pos16] = (short)(pk_reg - 32768);
       if (tile + 4 < ntiles) pk_reg = tile_row_orig(tile + 4);
     }
     if (tile + 1 < ntiles) {
@@ -229,31 +259,34 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       if (act[kb]) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+        bf16x8 ka[D / 16];  // all K operands of the block are requested before the first product
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (32 * kb + c32) * C::KSTR + 16 * kk + 8 * g2);
-          sacc[kb] = mfma_bf16(a, qf[kk], sacc[kb]);
-        }
+        for (int kk = 0; kk < D / 16; ++kk)
+          ka[kk] = *reinterpret_cast<const bf16x8*>(Ks + (32 * kb + c32) * C::KSTR + 16 * kk + 8 * g2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) sacc[kb] = mfma_bf16(ka[kk], qf[kk], sacc[kb]);
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[kb][i] = -INFINITY;
       }
     }
 
+    auto causal_to_neg_inf = [&](f32x16& a, int kb) {
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        const int4 pk = *reinterpret_cast<const int4*>(pk_lds + 32 * kb + 8 * mq + 4 * g2);
+        if (pk.x > orig_q) a[4 * mq + 0] = -INFINITY;
+        if (pk.y > orig_q) a[4 * mq + 1] = -INFINITY;
+        if (pk.z > orig_q) a[4 * mq + 2] = -INFINITY;
+        if (pk.w > orig_q) a[4 * mq + 3] = -INFINITY;
+      }
+    };
     // ---- mask.  Accumulator i of block kb is key row 32*kb + 8*(i/4) + 4*g2 + i%4 of the tile.
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (!act[kb]) continue;
-      if (causal) {
-#pragma unroll
-        for (int mq = 0; mq < 4; ++mq) {
-          const int4 pk = *reinterpret_cast<const int4*>(pk_lds + 32 * kb + 8 * mq + 4 * g2);
-          if (pk.x > orig_q) sacc[kb][4 * mq + 0] = -INFINITY;
-          if (pk.y > orig_q) sacc[kb][4 * mq + 1] = -INFINITY;
-          if (pk.z > orig_q) sacc[kb][4 * mq + 2] = -INFINITY;
-          if (pk.w > orig_q) sacc[kb][4 * mq + 3] = -INFINITY;
-        }
-      }
+      if (CAUSAL == CAUSAL_I32) causal_to_neg_inf(sacc[kb], kb);
       if (!inside[kb]) {
         const int base = t0 + 32 * kb + 4 * g2 - s + Ll;
 #pragma unroll
@@ -273,6 +306,20 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     if (__any(mx > m_ref + lazy)) {  // (-inf + lazy = -inf: the first visible key always triggers)
+      if (CAUSAL == CAUSAL_I16) {
+        // mx still counts later keys (their probabilities are cleared further down, whatever they
+        // are): take the maximum over the visible keys only before moving the reference
+        float mv = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          if (!act[kb]) continue;
+          f32x16 t = sacc[kb];
+          causal_to_neg_inf(t, kb);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mv = fmaxf(mv, t[i]);
+        }
+        mx = fmaxf(mv, __shfl_xor(mv, 32));
+      }
       const float m_new = fmaxf(m_ref, mx);
       const float alpha = (mx > m_ref + lazy) ? __builtin_amdgcn_exp2f((m_ref - m_new) * cs) : 1.f;
       if (mx > m_ref + lazy) m_ref = m_new;
@@ -287,14 +334,36 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (!act[kb]) continue;
-      float pe[16];
+      if (CAUSAL == CAUSAL_I16) {
+        // pair e of the lane = accumulators 2e, 2e+1; the ring keeps their biased indices as one dword
+        typedef short s16x2 __attribute__((ext_vector_type(2)));
+        const s16x2 oq1 = {(short)(orig_q + 1 - 32768), (short)(orig_q + 1 - 32768)};
+        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+        const uint32_t* pk16 = reinterpret_cast<const uint32_t*>(ring16 + (tile & (C::RING - 1)) * BN) + 16 * kb + 8 * g2;
+        const u32x4 ia = *reinterpret_cast<const u32x4*>(pk16), ib = *reinterpret_cast<const u32x4*>(pk16 + 4);
+        u32x4 w[2];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], cs, -mc));
-        l_run += pe[i];
+        for (int e = 0; e < 8; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][2 * e], cs, -mc));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][2 * e + 1], cs, -mc));
+          const s16x2 pk2 = __builtin_bit_cast(s16x2, e < 4 ? ia[e & 3] : ib[e & 3]);
+          const s16x2 later = __builtin_elementwise_sub_sat(pk2, oq1);  // >= 0 for keys after the query
+          const uint32_t pp = pack_bf16(p0, p1) & __builtin_bit_cast(uint32_t, later >> (short)15);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pp), ones, l_run, false);
+          w[e >> 2][e & 3] = pp;
+        }
+        pf[kb][0] = __builtin_bit_cast(bf16x8, w[0]);
+        pf[kb][1] = __builtin_bit_cast(bf16x8, w[1]);
+      } else {
+        float pe[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], cs, -mc));
+          l_run += pe[i];
+        }
+        pf[kb][0] = pack_b_operand(pe);
+        pf[kb][1] = pack_b_operand(pe + 8);
       }
-      pf[kb][0] = pack_b_operand(pe);
-      pf[kb][1] = pack_b_operand(pe + 8);
     }
 
     // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts tile rows 32kb+16c+{0..3,8..11}+4*g2 (+4 for the
@@ -351,11 +420,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
         *reinterpret_cast<u32x2*>(Os + c32 * C::KSTR + 32 * db + 8 * mq + 4 * g2) = w;
       }
     __syncthreads();
-    constexpr int NP = 32 / C::WRPP;
-    const int chunk16 = lane % C::VPR;
     int dst[NP];
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) dst[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
+    for (int pass = 0; pass < NP; ++pass) dst[pass] = rowstash[wave * 32 + pass * C::WRPP + lane / C::VPR];
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) {
       const int row = pass * C::WRPP + lane / C::VPR;
@@ -401,11 +468,20 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
   const long total = (long)num_qt * p.Hq * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks), block(NT);
+  const int mode = !p.causal ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
+#define SA_LAUNCH_FWD(PERM_, MODE_) \
+  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_>), grid, block, 0, st, p, num_qt, total)
   if (p.perm) {
-    hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, true>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+    if (mode == CAUSAL_NONE) SA_LAUNCH_FWD(true, CAUSAL_NONE);
+    else if (mode == CAUSAL_I16) SA_LAUNCH_FWD(true, CAUSAL_I16);
+    else SA_LAUNCH_FWD(true, CAUSAL_I32);
   } else {
-    hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, false>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+    if (mode == CAUSAL_NONE) SA_LAUNCH_FWD(false, CAUSAL_NONE);
+    else if (mode == CAUSAL_I16) SA_LAUNCH_FWD(false, CAUSAL_I16);
+    else SA_LAUNCH_FWD(false, CAUSAL_I32);
   }
+#undef SA_LAUNCH_FWD
   return hipGetLastError();
 }
 
@@ -416,6 +492,7 @@ hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (p.n < 1 || p.B < 1 || p.Hq < 1 || p.Hkv < 1 || p.g * p.Hkv != p.Hq) return hipErrorInvalidValue;
   if (p.win.L < 0 || p.win.R < 0 || p.win.L >= p.n || p.win.R >= p.n) return hipErrorInvalidValue;
   if (p.win.circular && p.win.L + p.win.R + 1 > p.n) return hipErrorInvalidValue;
+  if ((long)p.n * p.d * 2 >= (1L << 31)) return hipErrorNotSupported;  // 32-bit row offsets inside a head
   if (p.gate_mode && (!p.gate_this || !p.gate_other || !p.Y_other_f32 || !p.Yout)) return hipErrorInvalidValue;
   if (p.d == 64) return launch_t<64>(p, st);
   if (p.d == 128) return launch_t<128>(p, st);

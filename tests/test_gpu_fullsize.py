@@ -57,7 +57,7 @@ def fwd_fullsize(name, rows_per_head):
         ma, rl = U.assert_close(pick(Y, rows), Yr, "bf16", f"{name} Y rows (window {window})")
         ri = torch.from_numpy(rows.astype(np.int64)).to(U.DEV)
         la = np.abs(L[ri[:, 0], ri[:, 1], ri[:, 2]].cpu().numpy().astype(np.float64) - Lr).max()
-        assert la <= 2e-3, la
+        assert la <= 4e-3, la
         print(f"  window {window}: {rows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e} lse {la:.1e}", flush=True)
 
 

@@ -11,10 +11,16 @@ CIRC, LIN, ONE = 0, 1, 2
 
 
 def run_fwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed=0, identity=False,
-            use_swa_entry=False):
+            use_swa_entry=False, k_growth=0.0):
     from oracle import binding as orc
     from paper_2604_00754_amd import binding as sa
     wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, identity=identity)
+    if k_growth:  # keys grow with their original position: later (masked) keys outscore the visible ones
+        from paper_2604_00754_amd import synth
+        ramp = (1.0 + k_growth * np.arange(n, dtype=np.float32) / n)[None, None, :, None]
+        x["K"] = (x["K"] * ramp).astype(np.float32)
+        if dtype == "bf16":
+            x["K"] = synth.round_to_bf16(x["K"])
     print(f"case fwd B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} win{window} causal{causal} {dtype} "
           f"perm[{perm_B},{perm_H}] identity={identity}", flush=True)
     Yr, Lr = orc.sa_fwd(U.orc_desc(wl, window, causal), x["Q"], x["K"], x["V"], x["perm"])
@@ -30,7 +36,7 @@ def run_fwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed
     torch.cuda.synchronize()
     U.assert_close(U.to_np64(Y), Yr, dtype, "Y")
     la = np.abs(U.to_np64(L) - Lr).max()
-    assert la <= (2e-3 if dtype == "bf16" else 1e-5), f"LSE max-abs {la:.3e}"
+    assert la <= (4e-3 if dtype == "bf16" else 1e-5), f"LSE max-abs {la:.3e}"
 
 
 def test_tiny_f32_config():
@@ -74,6 +80,19 @@ def test_bf16_swa_entry_and_identity():
 def test_bf16_gqa_shared_and_per_batch_perm():
     run_fwd(2, 8, 2, 1100, 128, 256, CIRC, 1, "bf16", perm_B=2, perm_H=1, seed=40)
     run_fwd(2, 8, 2, 600, 64, 256, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=41)
+
+
+def test_bf16_later_keys_dominate():
+    """Scores of later (causally masked) keys far above the visible ones: the packed 16-bit mask clears
+    their probabilities after the exponential, so they must neither move the softmax reference nor leak
+    an overflow into the row sums."""
+    run_fwd(1, 2, 2, 1500, 64, 256, CIRC, 1, "bf16", seed=50, k_growth=40.0)
+    run_fwd(1, 2, 1, 900, 128, 128, CIRC, 1, "bf16", perm_H=2, seed=51, k_growth=25.0)
+
+
+def test_bf16_long_sequence_uses_32bit_indices():
+    """n > 65535: original positions no longer fit the 16-bit mask path."""
+    run_fwd(1, 1, 1, 66000, 64, 64, CIRC, 1, "bf16", seed=52)
 
 
 def test_pretraining_shape_sample():

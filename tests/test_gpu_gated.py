@@ -48,7 +48,7 @@ def run_gated(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gate_dt
     if keep:
         U.assert_close(U.to_np64(Ysa), ref["Ysa"], dtype, "Y_sa")
         U.assert_close(U.to_np64(Yswa), ref["Yswa"], dtype, "Y_swa")
-        tol = 2e-3 if dtype == "bf16" else 1e-5
+        tol = 4e-3 if dtype == "bf16" else 1e-5
         assert np.abs(U.to_np64(Lsa) - ref["LSEsa"]).max() <= tol
         assert np.abs(U.to_np64(Lswa) - ref["LSEswa"]).max() <= tol
     if saturate and keep:
