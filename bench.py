@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per sa_fwd launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.000, WRITE_SIZE by 1.000 against a 1 GiB copy); see profiles/fwd_mfma_bf16_d128_qwen3_8b_prefill_32k.md
-MEASURED_TRAFFIC_BYTES = 397352 * 1024 + 302841 * 1024
+MEASURED_TRAFFIC_BYTES = 396764 * 1024 + 303623 * 1024
 
 
 def band_slots(n, w, window):
@@ -159,7 +159,7 @@ def main():
     e = 2
     alg_bytes = wl.B * wl.n * (wl.Hq * 2 * wl.d * e + wl.Hkv * 2 * wl.d * e + wl.Hq * 4) + wl.n * 4
     tflops = band_flop / (launch_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128>", "achieved": tflops,
+    roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128, true, 2>", "achieved": tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms}
     gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
