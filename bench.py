@@ -103,6 +103,28 @@ def training_ops(sa, synth, dev, reps):
         "gated_fwdbwd_tokens_per_s": B * n / ((t_gfwd + t_gbwd) * 1e-3)}}
 
 
+def long_prefill_ops(sa, synth, dev, reps):
+    """Side measurement: the long-prefill shape (B=1, 32 query / 4 KV heads, d=128, n=131072, w=1024),
+    SA forward and plain SWA forward side by side."""
+    wl = synth.WORKLOADS["qwen3_30b_prefill_128k"]
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.BASE_SEED + 2)
+    rn = lambda shape: torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+    Q, K, V = rn((wl.B, wl.Hq, wl.n, wl.d)), rn((wl.B, wl.Hkv, wl.n, wl.d)), rn((wl.B, wl.Hkv, wl.n, wl.d))
+    perm = torch.from_numpy(synth.permutations(1, 1, wl.n)).to(dev)
+    Y = torch.empty_like(Q)
+    dsa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+    dswa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
+    _, t_sa = time_op(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Y, None), reps, 1)
+    _, t_swa = time_op(lambda: sa.swa_fwd(dswa, Q, K, V, Y, None), reps, 1)
+    flop_sa = 4.0 * wl.n * band_slots(wl.n, wl.w, 0) * wl.d * wl.B * wl.Hq
+    return {"long_prefill_128k": {
+        "shape": "B1 Hq32 Hkv4 n131072 d128 w1024 bf16",
+        "sa_fwd_ms": t_sa, "sa_fwd_tokens_per_s": wl.B * wl.n / (t_sa * 1e-3),
+        "sa_fwd_band_tflops": flop_sa / (t_sa * 1e-3) / 1e12,
+        "swa_fwd_ms": t_swa, "swa_fwd_tokens_per_s": wl.B * wl.n / (t_swa * 1e-3)}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,8 +196,16 @@ def main():
         Y2 = torch.empty_like(Q)
         _, swa_ms = time_op(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
         other = {"swa_fwd_ms": swa_ms, "swa_fwd_tokens_per_s": wl.B * wl.n / (swa_ms * 1e-3)}
+        # gather + scatter with (almost) no attention work: w = 1, every token sees itself only
+        w1_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, 1, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16,
+                               0.0, 1, 1)
+        _, w1_ms = time_op(lambda: sa.sa_fwd(w1_desc, Q, K, V, perm, Y2, None), max(10, args.steps // 4), 5)
+        other.update({"gather_scatter_w1_ms": w1_ms,
+                      "gather_scatter_w1_GBps": alg_bytes / (w1_ms * 1e-3) / 1e9,
+                      "gather_scatter_w1_frac_hbm": alg_bytes / (w1_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
         del Y2
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
+        other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))
 
     out = {"metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
