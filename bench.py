@@ -47,8 +47,34 @@ def time_op(fn, steps, warmup):
         b.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_launch_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
-    return wall, per_launch_ms
+    samples = [a.elapsed_time(b) for a, b in ev]
+    time_op.last_samples_ms = samples
+    return wall, float(np.mean(samples))
+
+
+def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
+    """Flop of the matrix instructions the forward kernel issues at this shape (symmetric circular
+    window): per wave (32 query slots) every 32-key block of the workgroup's tiles that any of its
+    queries can see, each costing 2 * (d/16) MFMAs of 32x32x16."""
+    h = (w - 1) // 2
+    L, R = min(h, (n - 1) // 2), 0
+    R = min(h, n - 1 - L)
+    per_block = 2 * (d // 16) * 2 * 32 * 32 * 16
+    total_blocks = 0
+    for p0 in range(0, n, BM):
+        q_last = min(p0 + BM - 1, n - 1)
+        t_lo, t_hi = p0 - L, q_last + R
+        ntiles = (t_hi - t_lo + BN) // BN
+        for wave in range(BM // 32):
+            s_w0 = p0 + 32 * wave
+            if s_w0 >= n:
+                continue  # such a wave still runs, on clamped rows; not counted
+            for blk in range(2 * ntiles):
+                tb0 = t_lo + 32 * blk
+                dmax, dmin = tb0 + 31 - s_w0, tb0 - (s_w0 + 31)
+                if not (dmax < -L or dmin > R) and tb0 <= t_hi:
+                    total_blocks += 1
+    return float(total_blocks) * per_block * B * Hq
 
 
 def cpu_baseline(wl, Q, K, V, perm, rows_per_head):
@@ -61,8 +87,12 @@ def cpu_baseline(wl, Q, K, V, perm, rows_per_head):
     t0 = time.perf_counter()
     Y, _ = orc.sa_fwd_rows(c, Q64, K64, V64, perm.cpu().numpy(), rows)
     dt = time.perf_counter() - t0
+    # pairs the mask leaves visible (the permutation is shared by the heads: count one head)
+    c1 = orc.desc(1, 1, 1, wl.n, wl.d, wl.w, orc.WIN_SYM_CIRCULAR, 1, 1, 1)
+    visible_pairs = int(orc.visible_count(c1, perm.cpu().numpy()).sum())
     tokens = rows.shape[0] / wl.Hq  # one token = one position across all query heads
     return {"value": tokens / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "useful_flop": 4.0 * wl.d * visible_pairs * wl.B * wl.Hq,
             "sample": f"{rows_per_head} of {wl.n} query rows per head, all {wl.Hq} heads "
                       f"({rows.shape[0]} rows, {dt:.1f} s)"}, rows, Y
 
@@ -172,6 +202,7 @@ def main():
         sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
 
     wall, launch_ms = time_op(step, args.steps, args.warmup)
+    launch_samples = list(time_op.last_samples_ms)
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = wl.B * wl.n / (wall / args.steps)
     assert torch.isfinite(Y.float()).all().item(), "sa_fwd produced non-finite values"
@@ -183,7 +214,10 @@ def main():
     tflops = band_flop / (launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128, true, 2>", "achieved": tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms}
+                "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
+                "median_launch_ms": float(np.median(launch_samples)), "min_launch_ms": float(np.min(launch_samples)),
+                "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq),
+                "caches": "not flushed between launches (see other_ops.cold_cache_ms)"}
     gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
     roofline_hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": gbs / PEAK_HBM_GBS, "algorithmic_bytes": alg_bytes}
@@ -203,6 +237,26 @@ def main():
         other.update({"gather_scatter_w1_ms": w1_ms,
                       "gather_scatter_w1_GBps": alg_bytes / (w1_ms * 1e-3) / 1e9,
                       "gather_scatter_w1_frac_hbm": alg_bytes / (w1_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        # the ceiling for that: gather + scatter alone (sa_permuted_copy), same rows, same index tensor
+        _, pc_ms = time_op(lambda: sa.sa_permuted_copy(desc, Q, K, V, perm, Y2), max(10, args.steps // 4), 5)
+        pc_bytes = alg_bytes - wl.B * wl.Hq * wl.n * 4  # no LSE
+        other.update({"permuted_copy_ms": pc_ms, "permuted_copy_GBps": pc_bytes / (pc_ms * 1e-3) / 1e9,
+                      "permuted_copy_frac_hbm": pc_bytes / (pc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        # the headline launch with cold caches: a 1 GiB device copy between launches evicts L2 and MALL
+        if copy_src is None:
+            cs = torch.zeros(256 * 1024 * 1024, device=dev, dtype=torch.float32)
+            cd = torch.empty_like(cs)
+            cold = []
+            for _ in range(10):
+                cd.copy_(cs)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
+                b.record()
+                torch.cuda.synchronize()
+                cold.append(a.elapsed_time(b))
+            other["cold_cache_ms"] = float(np.median(cold))
+            del cs, cd
         del Y2
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
         other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))

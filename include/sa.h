@@ -89,6 +89,16 @@ sa_status sa_check_perm(const sa_desc* desc, const int32_t* perm, void* ws, size
 sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                  const int32_t* perm, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement helper: the gather and the scatter of Alg. 1 (Sec. 3.3, the two index operations around
+ * the attention) with no attention in between.  For every (b, hq, slot p), with i = perm[p]:
+ *   Y[b,hq,i,:] = Q[b,hq,i,:]                                   if hq is not the first head of its KV group
+ *   Y[b,hq,i,:] = Q[b,hq,i,:] + K[b,hk,i,:] + V[b,hk,i,:]       if it is   (sum in fp32, rounded once)
+ * so every row of Q, K and V is read once through perm and every row of Y written once through it:
+ * the bytes sa_fwd must move (without LSE), as the ceiling for rows of 2*d bytes reached through the
+ * index tensor.  bf16 only (SA_ERR_UNSUPPORTED otherwise).  perm NULL = identity.  No workspace. */
+sa_status sa_permuted_copy(const sa_desc* desc, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, void* Y, void* stream);
+
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                   void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);

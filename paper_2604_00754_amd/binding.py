@@ -17,7 +17,7 @@ SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
-           "gated_sa_swa_fwd", "sa_bwd")
+           "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy")
 
 
 class sa_desc(C.Structure):
@@ -49,6 +49,8 @@ def _load():
     lib.sa_check_perm.argtypes = [dp, ip, vp, sz, vp]
     lib.sa_fwd.restype = C.c_int
     lib.sa_fwd.argtypes = [dp, vp, vp, vp, ip, vp, vp, vp, sz, vp]
+    lib.sa_permuted_copy.restype = C.c_int
+    lib.sa_permuted_copy.argtypes = [dp, vp, vp, vp, ip, vp, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -99,6 +101,11 @@ def sa_check_perm(desc, perm, ws):
 def sa_fwd(desc, Q, K, V, perm, Y, LSE=None):
     _check(_lib.sa_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(Y), _ptr(LSE),
                        None, 0, _stream()), "sa_fwd")
+
+
+def sa_permuted_copy(desc, Q, K, V, perm, Y):
+    _check(_lib.sa_permuted_copy(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(Y), _stream()),
+           "sa_permuted_copy")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

@@ -169,6 +169,17 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   return hip_status(run_fwd(c, p, (hipStream_t)stream));
 }
 
+sa_status sa_permuted_copy(const sa_desc* c, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, void* Y, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Q || !K || !V || !Y) return SA_ERR_NULL;
+  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  Pass p = make_pass(c, Q, K, V, perm);
+  p.Y = Y;
+  return hip_status(sa::launch_permuted_copy_bf16(p, (hipStream_t)stream));
+}
+
 sa_status swa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, void* Y, float* LSE,
                   void* ws, size_t ws_bytes, void* stream) {
   return sa_fwd(c, Q, K, V, nullptr, Y, LSE, ws, ws_bytes, stream);

@@ -59,6 +59,8 @@ hipError_t launch_bwd_rowwise_f32(const Pass& p, hipStream_t st);
 hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st);
 hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st);
 
+hipError_t launch_permuted_copy_bf16(const Pass& p, hipStream_t st);
+
 // helpers in sa_misc.hip
 hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag,
                              hipStream_t st);

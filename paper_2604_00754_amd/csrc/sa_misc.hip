@@ -27,6 +27,64 @@ __global__ void check_perm_kernel(const int32_t* __restrict__ perm, size_t total
   }
 }
 
+// The gather and the scatter of Alg. 1 without the attention in between (a measurement helper: the
+// ceiling for rows of 2*d bytes addressed through the index tensor).  One group of LPR lanes per
+// (b, hq, slot): Y[perm[p]] = Q[perm[p]] (+ K[perm[p]] + V[perm[p]] for the first query head of a KV
+// group, so that every K and V row is read once per group as in the attention kernels).  Four rows
+// per thread are in flight.
+template <int LPR>
+__global__ __launch_bounds__(256) void permuted_copy_bf16_kernel(const Pass p, const long rows) {
+  constexpr int RPT = 4;
+  const int sub = threadIdx.x % LPR;
+  const long group = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const long groups = (long)gridDim.x * 256 / LPR;
+  const int d = LPR * 8;
+  for (long r0 = group; r0 < rows; r0 += groups * RPT) {
+    long r[RPT];
+    int src[RPT];
+    bool ok[RPT];
+#pragma unroll
+    for (int j = 0; j < RPT; ++j) {
+      r[j] = r0 + j * groups;
+      ok[j] = r[j] < rows;
+      const long rr = ok[j] ? r[j] : 0;
+      const int slot = (int)(rr % p.n);
+      const long bh = rr / p.n;
+      const int hq = (int)(bh % p.Hq), b = (int)(bh / p.Hq);
+      src[j] = p.perm ? p.perm[(size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * p.n + slot] : slot;
+    }
+    u32x4 q[RPT], k[RPT], v[RPT];
+    bool lead[RPT];
+#pragma unroll
+    for (int j = 0; j < RPT; ++j) {
+      const long rr = ok[j] ? r[j] : 0;
+      const long bh = rr / p.n;
+      const int hq = (int)(bh % p.Hq), b = (int)(bh / p.Hq);
+      lead[j] = hq % p.g == 0;
+      const size_t qoff = ((size_t)bh * p.n + src[j]) * d + sub * 8;
+      const size_t koff = (((size_t)b * p.Hkv + hq / p.g) * p.n + src[j]) * d + sub * 8;
+      q[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.Q) + qoff);
+      if (lead[j]) {
+        k[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.K) + koff);
+        v[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.V) + koff);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < RPT; ++j) {
+      if (!ok[j]) continue;
+      u32x4 o = q[j];
+      if (lead[j]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          o[e] = pack_bf16(bf16lo(q[j][e]) + bf16lo(k[j][e]) + bf16lo(v[j][e]),
+                           bf16hi(q[j][e]) + bf16hi(k[j][e]) + bf16hi(v[j][e]));
+      }
+      const size_t qoff = ((size_t)(r[j] / p.n) * p.n + src[j]) * d + sub * 8;
+      *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.Y) + qoff) = o;
+    }
+  }
+}
+
 template <int LPR>  // lanes per row, each lane owns 16 bytes of the row
 __device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
@@ -166,6 +224,19 @@ hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, 
   if (e != hipSuccess) return e;
   const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
   hipLaunchKernelGGL(check_perm_kernel, dim3(blocks), dim3(256), 0, st, perm, total, n, seen, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_permuted_copy_bf16(const Pass& p, hipStream_t st) {
+  if (p.n < 1 || p.B < 1 || p.Hq < 1 || p.Hkv < 1 || p.g * p.Hkv != p.Hq || !p.Q || !p.K || !p.V || !p.Y)
+    return hipErrorInvalidValue;
+  if (!(p.d == 64 || p.d == 128)) return hipErrorNotSupported;
+  const long rows = (long)p.B * p.Hq * p.n;
+  const int lpr = p.d / 8;
+  const long want = (rows * lpr + 256 * 4 - 1) / (256 * 4);  // four rows per lane group
+  const unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 0x7fffffffL ? 0x7fffffffL : want));
+  if (p.d == 64) hipLaunchKernelGGL(permuted_copy_bf16_kernel<8>, dim3(blocks), dim3(256), 0, st, p, rows);
+  else hipLaunchKernelGGL(permuted_copy_bf16_kernel<16>, dim3(blocks), dim3(256), 0, st, p, rows);
   return hipGetLastError();
 }
 
