@@ -155,6 +155,50 @@ def long_prefill_ops(sa, synth, dev, reps):
         "swa_fwd_ms": t_swa, "swa_fwd_tokens_per_s": wl.B * wl.n / (t_swa * 1e-3)}}
 
 
+def table3_sweep(sa, synth, dev):
+    """Sec. 4.3 / Table 3 on this GPU: attention forward + backward in isolation, B=16, H=16, d=64,
+    w=256, bf16, n = 2K ... 32K: single-path SA, plain causal SWA, gated SA+SWA, and full causal
+    attention run through the same kernels with a window that covers the whole ring."""
+    B, H, d, w = 16, 16, 64, 256
+    out = []
+    for n in (2048, 4096, 8192, 16384, 32768):
+        g = torch.Generator(device=dev)
+        g.manual_seed(synth.BASE_SEED + n)
+        rn = lambda shape, dt=torch.bfloat16: torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(dt)
+        Q, K, V, dY = (rn((B, H, n, d)) for _ in range(4))
+        ga, gl = rn((B, H, n), torch.float32), rn((B, H, n), torch.float32)
+        perm = torch.from_numpy(synth.permutations(1, 1, n)).to(dev)
+        Y, Ysa, Yswa, dQ, dK, dV = (torch.empty_like(Q) for _ in range(6))
+        Lsa = torch.empty((B, H, n), device=dev, dtype=torch.float32)
+        Lswa, dga, dgl = torch.empty_like(Lsa), torch.empty_like(ga), torch.empty_like(gl)
+        dsa = sa.make_desc(B, H, H, n, d, w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+        dswa = sa.make_desc(B, H, H, n, d, w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
+        dfull = sa.make_desc(B, H, H, n, d, n, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
+        wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=dev, dtype=torch.uint8)
+        wsb = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=dev, dtype=torch.uint8)
+
+        def fwd_bwd(desc, pm):
+            sa.sa_fwd(desc, Q, K, V, pm, Ysa, Lsa)
+            sa.sa_bwd(desc, None, Q, K, V, pm, None, None, Ysa, None, Lsa, None, dY, dQ, dK, dV, None, None, wsb)
+
+        def gated():
+            sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
+            sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY, dQ, dK, dV, dga, dgl, wsb)
+
+        reps = 10 if n <= 8192 else 5
+        _, t_sa = time_op(lambda: fwd_bwd(dsa, perm), reps, 2)
+        _, t_swa = time_op(lambda: fwd_bwd(dswa, None), reps, 2)
+        _, t_g = time_op(gated, reps, 2)
+        _, t_full = time_op(lambda: fwd_bwd(dfull, None), 2 if n >= 16384 else 4, 1)
+        out.append({"n": n, "sa_fwdbwd_ms": t_sa, "swa_fwdbwd_ms": t_swa, "gated_sa_swa_fwdbwd_ms": t_g,
+                    "full_causal_fwdbwd_ms": t_full, "full_over_sa": t_full / t_sa, "gated_over_sa": t_g / t_sa})
+        print(f"table3 n={n}: SA {t_sa:.3f} ms  SWA {t_swa:.3f}  gated {t_g:.3f}  full {t_full:.2f}  "
+              f"full/SA {t_full / t_sa:.1f}x", file=sys.stderr, flush=True)
+        del Q, K, V, dY, Y, Ysa, Yswa, dQ, dK, dV, wsf, wsb
+        torch.cuda.empty_cache()
+    return {"table3_sweep": {"shape": "B16 H16 d64 w256 bf16, attention forward+backward", "rows": out}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,6 +210,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy before and between steps (a known-size kernel "
                          "for scaling the FETCH_SIZE / WRITE_SIZE counters; it also empties the caches)")
+    ap.add_argument("--table3", action="store_true",
+                    help="instead of the headline step, run the sequence-length sweep of Sec. 4.3 / Table 3 "
+                         "(SA, SWA, gated, full attention; forward + backward) and print it as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -178,8 +225,11 @@ def main():
     from paper_2604_00754_amd import binding as sa
     from paper_2604_00754_amd import synth
 
-    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
     dev = "cuda:0"
+    if args.table3:
+        print(json.dumps(table3_sweep(sa, synth, dev)))
+        return
+    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
     g = torch.Generator(device=dev)
     g.manual_seed(synth.BASE_SEED)
     Q = torch.randn((wl.B, wl.Hq, wl.n, wl.d), device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
