@@ -176,3 +176,19 @@ def gate_bwd(c, per_dim, dY, gsa, gswa, Ysa=None, Yswa=None):
     _check(lib().orc_gate_bwd(C.byref(c), int(per_dim), _p(dY), _p(gsa), _p(gswa), _p(Ysa), _p(Yswa),
                               _p(da), _p(dl), _p(dga), _p(dgl)), "orc_gate_bwd")
     return da, dl, dga, dgl
+
+
+def gate_proj_fwd(c, Ysa, Yswa, Wsa, Wswa, want_logits=False):
+    """Eq. 6 + Eq. 5.  Returns Y, or (Y, logits_sa, logits_swa) with want_logits; Yswa = Wswa = None
+    selects the single-path gate."""
+    qs, dm = (c.B, c.Hq, c.n, c.d), c.Hq * c.d
+    Ysa, Wsa = _f64(Ysa, qs), _f64(Wsa, (dm, dm))
+    dual = Yswa is not None
+    if dual:
+        Yswa, Wswa = _f64(Yswa, qs), _f64(Wswa, (dm, dm))
+    Y = np.empty(qs, np.float64)
+    La = np.empty(qs, np.float64) if want_logits else None
+    Lb = np.empty(qs, np.float64) if want_logits and dual else None
+    _check(lib().orc_gate_proj_fwd(C.byref(c), _p(Ysa), _p(Yswa) if dual else None, _p(Wsa),
+                                   _p(Wswa) if dual else None, _p(Y), _p(La), _p(Lb)), "orc_gate_proj_fwd")
+    return (Y, La, Lb) if want_logits else Y

@@ -582,3 +582,32 @@ int orc_sa_bwd_dkv_rows(const orc_desc* c, const double* Q, const double* K, con
   free(inv);
   return 0;
 }
+
+/* ---------------------------------------------------------------- gate projections (Eq. 6, Eq. 5) */
+int orc_gate_proj_fwd(const orc_desc* c, const double* Ysa, const double* Yswa,
+                      const double* Wsa, const double* Wswa, double* Y, double* Lsa, double* Lswa) {
+  if (!desc_ok(c) || !Ysa || !Wsa || !Y) return -1;
+  if ((Yswa == NULL) != (Wswa == NULL)) return -1;
+  const int64_t n = c->n, d = c->d, H = c->Hq, dm = H * d;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int64_t b = 0; b < c->B; ++b) {
+    for (int64_t i = 0; i < n; ++i) {
+      for (int64_t o = 0; o < dm; ++o) {            /* output feature o = (ho, eo) */
+        const int64_t ho = o / d, eo = o % d;
+        const int64_t at = ((b * H + ho) * n + i) * d + eo;
+        double za = 0.0, zb = 0.0;
+        for (int64_t k = 0; k < dm; ++k) {          /* input feature k = (hk, ek) */
+          const int64_t src = ((b * H + k / d) * n + i) * d + k % d;
+          za += Wsa[o * dm + k] * Ysa[src];
+          if (Yswa) zb += Wswa[o * dm + k] * Yswa[src];
+        }
+        double y = sigmoid(za) * Ysa[at];
+        if (Yswa) y += sigmoid(zb) * Yswa[at];
+        Y[at] = y;
+        if (Lsa) Lsa[at] = za;
+        if (Lswa && Yswa) Lswa[at] = zb;
+      }
+    }
+  }
+  return 0;
+}

@@ -107,6 +107,17 @@ int orc_sa_bwd_dkv_rows(const orc_desc* c, const double* Q, const double* K, con
                         const int32_t* perm, const double* dY,
                         const int32_t* rows, int64_t nrows, double* dK_rows, double* dV_rows);
 
+/* Gate projections of the dual-path layer, Eq. 6 followed by Eq. 5 (Alg. 2, "Gated
+ * Combination").  Per token t = (b, i) let y_x[t] in R^{dm}, dm = Hq*d, be the
+ * concatenation over heads of Y_x[b,h,i,:].  Then
+ *   logit_x[t,:] = W_x y_x[t]     (W_x [dm,dm] row-major, row = output feature)
+ *   g_x = sigmoid(logit_x),   Y[t,:] = g_sa * y_sa[t] + g_swa * y_swa[t]   (element-wise)
+ * Y, Y_sa, Y_swa and the optional logit outputs L_sa, L_swa are [B,Hq,n,d] (feature
+ * (h,e) of a token lives at [b,h,i,e]).  Y_swa = W_swa = NULL selects the
+ * single-path attention gate of App. A: Y = sigmoid(W_sa y_sa) * y_sa. */
+int orc_gate_proj_fwd(const orc_desc* c, const double* Ysa, const double* Yswa,
+                      const double* Wsa, const double* Wswa, double* Y, double* Lsa, double* Lswa);
+
 #ifdef __cplusplus
 }
 #endif

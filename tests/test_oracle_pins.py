@@ -492,3 +492,39 @@ def test_synthetic_inputs_are_seeded_and_valid():
     r = synth.round_to_bf16(x)
     t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(r, t)
+
+
+# ------------------------------------------------------------------ gate projections (Eq. 6 + Eq. 5)
+
+def test_gate_projection_against_matmul_and_closed_forms():
+    """Eq. 6 over the model dimension (heads of a token concatenated), then Eq. 5.  Pinned to a library
+    matmul on the explicitly re-laid-out [B, n, H*d] tensors, and to closed forms: W = 0 gives both
+    gates 1/2; W = c*I gates every element by sigmoid(c*y); a W that reads one input feature only
+    gates a whole token by that feature; the single-path form is the dual form with a zero branch."""
+    B, H, n, d = 2, 3, 7, 4
+    dm = H * d
+    c = orc.desc(B, H, H, n, d, 4)
+    Ysa, Yswa = rnd((B, H, n, d), 301), rnd((B, H, n, d), 302)
+    Wsa, Wswa = rnd((dm, dm), 303) * 0.5, rnd((dm, dm), 304) * 0.5
+    sig = lambda x: 1 / (1 + np.exp(-x))
+    tok = lambda Y: Y.transpose(0, 2, 1, 3).reshape(B, n, dm)            # token-major [B, n, H*d]
+    back = lambda T: T.reshape(B, n, H, d).transpose(0, 2, 1, 3)
+    Y, La, Lb = orc.gate_proj_fwd(c, Ysa, Yswa, Wsa, Wswa, want_logits=True)
+    za, zb = tok(Ysa) @ Wsa.T, tok(Yswa) @ Wswa.T
+    np.testing.assert_allclose(La, back(za), atol=1e-13)
+    np.testing.assert_allclose(Lb, back(zb), atol=1e-13)
+    np.testing.assert_allclose(Y, back(sig(za) * tok(Ysa) + sig(zb) * tok(Yswa)), atol=1e-13)
+    # a transposed weight is a different map (catches W vs W^T)
+    assert np.abs(orc.gate_proj_fwd(c, Ysa, Yswa, Wsa.T.copy(), Wswa, False) - Y).max() > 1e-3
+    # closed forms
+    Z = np.zeros((dm, dm))
+    np.testing.assert_allclose(orc.gate_proj_fwd(c, Ysa, Yswa, Z, Z), 0.5 * (Ysa + Yswa), atol=1e-15)
+    I = np.eye(dm)
+    np.testing.assert_allclose(orc.gate_proj_fwd(c, Ysa, Yswa, 2.0 * I, -3.0 * I),
+                               sig(2.0 * Ysa) * Ysa + sig(-3.0 * Yswa) * Yswa, atol=1e-14)
+    E = np.zeros((dm, dm)); E[:, 5] = 1.0        # every output feature reads input feature 5 = (head 1, e 1)
+    g = sig(Ysa[:, 1, :, 1])[:, None, :, None]   # one gate value per token, broadcast over heads and e
+    np.testing.assert_allclose(orc.gate_proj_fwd(c, Ysa, Yswa, E, Z), g * Ysa + 0.5 * Yswa, atol=1e-14)
+    # single path (App. A attention gate) = dual path with a vanishing second branch
+    single = orc.gate_proj_fwd(c, Ysa, None, Wsa, None)
+    np.testing.assert_allclose(single, orc.gate_proj_fwd(c, Ysa, np.zeros_like(Ysa), Wsa, Wswa), atol=1e-15)
