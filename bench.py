@@ -122,9 +122,16 @@ def training_ops(sa, synth, dev, reps):
                                                     wsf), reps, 2)
     _, t_gbwd = time_op(lambda: sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY,
                                           dQ, dK, dV, dga, dgl, wsb), reps, 2)
+    # the gate projections of the paper's layer (Eq. 6 + Eq. 5) on the two branch outputs, d_model = H*d
+    dm = H * d
+    Wsa, Wswa = (rn((dm, dm), torch.float32).mul_(dm ** -0.5).to(torch.bfloat16) for _ in range(2))
+    _, t_gp = time_op(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y), reps, 2)
+    flop_gp = 2 * 2.0 * B * n * dm * dm
     W = band_slots(n, w, 0)
     flop_fb = 14.0 * n * W * d * B * H  # forward 4, backward 10 per (query, in-window slot, d)
     return {"pretrain_8k": {
+        "gate_proj_fwd_ms": t_gp, "gate_proj_fwd_tflops": flop_gp / (t_gp * 1e-3) / 1e12,
+        "gate_proj_fwd_frac_mfma_peak": flop_gp / (t_gp * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "shape": "B4 H16 n8192 d64 w256 bf16",
         "sa_fwd_ms": t_fwd, "sa_bwd_ms": t_bwd,
         "sa_fwdbwd_tokens_per_s": B * n / ((t_fwd + t_bwd) * 1e-3),

@@ -99,6 +99,18 @@ sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* 
 sa_status sa_permuted_copy(const sa_desc* desc, const void* Q, const void* K, const void* V,
                            const int32_t* perm, void* Y, void* stream);
 
+/* Gate projections of the dual-path layer: Eq. 6 followed by Eq. 5 (Alg. 2, "Gated Combination").
+ * Per token t = (b, i) let y_x[t] in R^{dm}, dm = Hq*d, be the concatenation over heads of
+ * Y_x[b,h,i,:] (feature (h,e) of a token lives at [b,h,i,e]).  Then
+ *   g_x[t,:] = sigmoid(W_x y_x[t]),     Y[t,:] = g_sa * y_sa[t] + g_swa * y_swa[t]   (element-wise)
+ * W_sa, W_swa: [dm, dm] row-major in the tensor dtype, row = output feature (the W_g of Eq. 6).
+ * Y_swa = W_swa = NULL selects the single-path attention gate of App. A: Y = sigmoid(W_sa y_sa) * y_sa.
+ * G_sa, G_swa (each may be NULL): the gate values g_x, [B,Hq,n,d] in the tensor dtype, for a backward.
+ * Y may not alias Y_sa or Y_swa.  bf16 with dm a multiple of 128 only (SA_ERR_UNSUPPORTED otherwise);
+ * of the descriptor only B, Hq, n, d and dtype are used.  No workspace. */
+sa_status sa_gate_proj_fwd(const sa_desc* desc, const void* Y_sa, const void* Y_swa, const void* W_sa,
+                           const void* W_swa, void* Y, void* G_sa, void* G_swa, void* stream);
+
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                   void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);

@@ -17,7 +17,7 @@ SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
-           "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy")
+           "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd")
 
 
 class sa_desc(C.Structure):
@@ -51,6 +51,8 @@ def _load():
     lib.sa_fwd.argtypes = [dp, vp, vp, vp, ip, vp, vp, vp, sz, vp]
     lib.sa_permuted_copy.restype = C.c_int
     lib.sa_permuted_copy.argtypes = [dp, vp, vp, vp, ip, vp, vp]
+    lib.sa_gate_proj_fwd.restype = C.c_int
+    lib.sa_gate_proj_fwd.argtypes = [dp] + [vp] * 8
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -106,6 +108,11 @@ def sa_fwd(desc, Q, K, V, perm, Y, LSE=None):
 def sa_permuted_copy(desc, Q, K, V, perm, Y):
     _check(_lib.sa_permuted_copy(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(Y), _stream()),
            "sa_permuted_copy")
+
+
+def sa_gate_proj_fwd(desc, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa=None, G_swa=None):
+    _check(_lib.sa_gate_proj_fwd(C.byref(desc), _ptr(Y_sa), _ptr(Y_swa), _ptr(W_sa), _ptr(W_swa), _ptr(Y),
+                                 _ptr(G_sa), _ptr(G_swa), _stream()), "sa_gate_proj_fwd")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

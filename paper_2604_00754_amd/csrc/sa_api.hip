@@ -180,6 +180,18 @@ sa_status sa_permuted_copy(const sa_desc* c, const void* Q, const void* K, const
   return hip_status(sa::launch_permuted_copy_bf16(p, (hipStream_t)stream));
 }
 
+sa_status sa_gate_proj_fwd(const sa_desc* c, const void* Y_sa, const void* Y_swa, const void* W_sa,
+                           const void* W_swa, void* Y, void* G_sa, void* G_swa, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Y_sa || !W_sa || !Y) return SA_ERR_NULL;
+  if ((Y_swa == nullptr) != (W_swa == nullptr)) return SA_ERR_NULL;
+  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  if (((long)c->Hq * c->d) % 128 != 0) return SA_ERR_UNSUPPORTED;  // whole 128-feature tiles
+  return hip_status(sa::launch_gate_proj_fwd_bf16(c->B, c->Hq, c->n, c->d, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa,
+                                                  G_swa, (hipStream_t)stream));
+}
+
 sa_status swa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, void* Y, float* LSE,
                   void* ws, size_t ws_bytes, void* stream) {
   return sa_fwd(c, Q, K, V, nullptr, Y, LSE, ws, ws_bytes, stream);

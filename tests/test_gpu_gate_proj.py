@@ -1,0 +1,77 @@
+"""GPU parity of sa_gate_proj_fwd (Eq. 6 + Eq. 5: gate projections over the model dimension and the
+gated sum) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(B, H, n, d, seed, dual=True, w_scale=None, want_gates=True):
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    dm = H * d
+    print(f"case gate_proj B{B} H{H} n{n} d{d} dm{dm} dual={dual}", flush=True)
+    rng = np.random.default_rng(synth.BASE_SEED + seed)
+    r16 = lambda a: synth.round_to_bf16(a.astype(np.float32))
+    Ysa = r16(rng.standard_normal((B, H, n, d)))
+    Yswa = r16(rng.standard_normal((B, H, n, d)))
+    s = w_scale if w_scale is not None else 1.0 / np.sqrt(dm)   # logits ~ N(0, 1)
+    Wsa, Wswa = r16(rng.standard_normal((dm, dm)) * s), r16(rng.standard_normal((dm, dm)) * s)
+    c = orc.desc(B, H, H, n, d, 4)
+    if dual:
+        Yr, La, Lb = orc.gate_proj_fwd(c, Ysa, Yswa, Wsa, Wswa, want_logits=True)
+    else:
+        Yr, La, Lb = orc.gate_proj_fwd(c, Ysa, None, Wsa, None, want_logits=True)
+    dev = lambda a: U.to_dev(a, "bf16")
+    tYsa, tWsa = dev(Ysa), dev(Wsa)
+    tYswa, tWswa = (dev(Yswa), dev(Wswa)) if dual else (None, None)
+    Y = torch.full_like(tYsa, float("nan"))
+    Ga = torch.full_like(tYsa, float("nan")) if want_gates else None
+    Gb = torch.full_like(tYsa, float("nan")) if want_gates and dual else None
+    desc = sa.make_desc(B, H, H, n, d, 4)
+    sa.sa_gate_proj_fwd(desc, tYsa, tYswa, tWsa, tWswa, Y, Ga, Gb)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(Y), Yr, "bf16", "Y")
+    if want_gates:
+        sig = lambda x: 1 / (1 + np.exp(-x))
+        U.assert_close(U.to_np64(Ga), sig(La), "bf16", "G_sa")
+        if dual:
+            U.assert_close(U.to_np64(Gb), sig(Lb), "bf16", "G_swa")
+
+
+@pytest.mark.parametrize("d,H", [(64, 2), (64, 6), (128, 1), (128, 3)])
+def test_gate_proj_dual_path(d, H):
+    run_case(2, H, 300, d, seed=d + H)          # ragged token tiles (300 = 2 * 128 + 44)
+
+
+def test_gate_proj_single_path_and_no_gate_outputs():
+    run_case(1, 4, 129, 64, seed=7, dual=False)
+    run_case(1, 2, 64, 128, seed=8, dual=True, want_gates=False)
+
+
+def test_gate_proj_saturating_and_zero_weights():
+    run_case(1, 2, 200, 64, seed=9, w_scale=2.0)    # |logits| ~ 20: gates saturate at 0 / 1
+    run_case(1, 2, 200, 64, seed=10, w_scale=0.0)   # both gates exactly 1/2
+
+
+def test_gate_proj_pretraining_width():
+    """d_model = 1024 (16 heads of 64) as in the paper's pre-training setup (App. A), a few token tiles."""
+    run_case(1, 16, 1000, 64, seed=11)
+
+
+def test_gate_proj_rejects_unsupported():
+    from paper_2604_00754_amd import binding as sa
+    t = torch.zeros((1, 1, 8, 64), device=U.DEV, dtype=torch.bfloat16)
+    w = torch.zeros((64, 64), device=U.DEV, dtype=torch.bfloat16)
+    with pytest.raises(sa.SaError) as e:  # dm = 64 is not a multiple of 128
+        sa.sa_gate_proj_fwd(sa.make_desc(1, 1, 1, 8, 64, 4), t, t, w, w, torch.empty_like(t))
+    assert e.value.status == sa.SA_ERR_UNSUPPORTED
+    with pytest.raises(sa.SaError) as e:  # second branch given without its weight
+        t2 = torch.zeros((1, 2, 8, 64), device=U.DEV, dtype=torch.bfloat16)
+        w2 = torch.zeros((128, 128), device=U.DEV, dtype=torch.bfloat16)
+        sa.sa_gate_proj_fwd(sa.make_desc(1, 2, 2, 8, 64, 4), t2, t2, w2, None, torch.empty_like(t2))
+    assert e.value.status == sa.SA_ERR_NULL
