@@ -192,3 +192,20 @@ def gate_proj_fwd(c, Ysa, Yswa, Wsa, Wswa, want_logits=False):
     _check(lib().orc_gate_proj_fwd(C.byref(c), _p(Ysa), _p(Yswa) if dual else None, _p(Wsa),
                                    _p(Wswa) if dual else None, _p(Y), _p(La), _p(Lb)), "orc_gate_proj_fwd")
     return (Y, La, Lb) if want_logits else Y
+
+
+def gate_proj_bwd(c, Ysa, Yswa, Wsa, Wswa, dY):
+    """Returns dict(dYsa, dWsa[, dYswa, dWswa])."""
+    qs, dm = (c.B, c.Hq, c.n, c.d), c.Hq * c.d
+    Ysa, Wsa, dY = _f64(Ysa, qs), _f64(Wsa, (dm, dm)), _f64(dY, qs)
+    dual = Yswa is not None
+    if dual:
+        Yswa, Wswa = _f64(Yswa, qs), _f64(Wswa, (dm, dm))
+    out = {"dYsa": np.empty(qs, np.float64), "dWsa": np.empty((dm, dm), np.float64)}
+    if dual:
+        out.update(dYswa=np.empty(qs, np.float64), dWswa=np.empty((dm, dm), np.float64))
+    _check(lib().orc_gate_proj_bwd(C.byref(c), _p(Ysa), _p(Yswa) if dual else None, _p(Wsa),
+                                   _p(Wswa) if dual else None, _p(dY), _p(out["dYsa"]),
+                                   _p(out.get("dYswa")), _p(out["dWsa"]), _p(out.get("dWswa"))),
+           "orc_gate_proj_bwd")
+    return out

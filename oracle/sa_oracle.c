@@ -611,3 +611,43 @@ int orc_gate_proj_fwd(const orc_desc* c, const double* Ysa, const double* Yswa,
   }
   return 0;
 }
+
+static void gate_proj_bwd_branch(const orc_desc* c, const double* Yx, const double* W, const double* dY,
+                                 double* dYx, double* dW) {
+  const int64_t n = c->n, d = c->d, H = c->Hq, dm = H * d;
+  for (int64_t e = 0; e < dm * dm; ++e) dW[e] = 0.0;
+  double* y = (double*)malloc(sizeof(double) * (size_t)dm);   /* one token, features concatenated */
+  double* dz = (double*)malloc(sizeof(double) * (size_t)dm);
+  double* g = (double*)malloc(sizeof(double) * (size_t)dm);
+  for (int64_t b = 0; b < c->B; ++b) {
+    for (int64_t i = 0; i < n; ++i) {
+      for (int64_t k = 0; k < dm; ++k) y[k] = Yx[((b * H + k / d) * n + i) * d + k % d];
+      for (int64_t o = 0; o < dm; ++o) {
+        double z = 0.0;
+        for (int64_t k = 0; k < dm; ++k) z += W[o * dm + k] * y[k];
+        g[o] = sigmoid(z);
+        const double dy_o = dY[((b * H + o / d) * n + i) * d + o % d];
+        dz[o] = dy_o * y[o] * g[o] * (1.0 - g[o]);
+      }
+      for (int64_t k = 0; k < dm; ++k) {
+        double acc = dY[((b * H + k / d) * n + i) * d + k % d] * g[k];
+        for (int64_t o = 0; o < dm; ++o) acc += W[o * dm + k] * dz[o];
+        dYx[((b * H + k / d) * n + i) * d + k % d] = acc;
+      }
+      for (int64_t o = 0; o < dm; ++o)
+        for (int64_t k = 0; k < dm; ++k) dW[o * dm + k] += dz[o] * y[k];
+    }
+  }
+  free(y); free(dz); free(g);
+}
+
+int orc_gate_proj_bwd(const orc_desc* c, const double* Ysa, const double* Yswa,
+                      const double* Wsa, const double* Wswa, const double* dY,
+                      double* dYsa, double* dYswa, double* dWsa, double* dWswa) {
+  if (!desc_ok(c) || !Ysa || !Wsa || !dY || !dYsa || !dWsa) return -1;
+  const int dual = Yswa != NULL;
+  if (dual != (Wswa != NULL) || dual != (dYswa != NULL) || dual != (dWswa != NULL)) return -1;
+  gate_proj_bwd_branch(c, Ysa, Wsa, dY, dYsa, dWsa);
+  if (dual) gate_proj_bwd_branch(c, Yswa, Wswa, dY, dYswa, dWswa);
+  return 0;
+}

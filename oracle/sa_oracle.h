@@ -118,6 +118,14 @@ int orc_sa_bwd_dkv_rows(const orc_desc* c, const double* Q, const double* K, con
 int orc_gate_proj_fwd(const orc_desc* c, const double* Ysa, const double* Yswa,
                       const double* Wsa, const double* Wswa, double* Y, double* Lsa, double* Lswa);
 
+/* Gradient of orc_gate_proj_fwd with respect to the branch outputs and the weights, given dY:
+ *   dz_x = dY * y_x * g_x * (1 - g_x),   dy_x = dY * g_x + W_x^T dz_x,   dW_x = sum_t dz_x[t] y_x[t]^T
+ * (g_x recomputed from y_x and W_x).  dYsa, dYswa [B,Hq,n,d]; dWsa, dWswa [dm,dm].  The *swa
+ * arguments are all NULL for the single path. */
+int orc_gate_proj_bwd(const orc_desc* c, const double* Ysa, const double* Yswa,
+                      const double* Wsa, const double* Wswa, const double* dY,
+                      double* dYsa, double* dYswa, double* dWsa, double* dWswa);
+
 #ifdef __cplusplus
 }
 #endif

@@ -528,3 +528,37 @@ def test_gate_projection_against_matmul_and_closed_forms():
     # single path (App. A attention gate) = dual path with a vanishing second branch
     single = orc.gate_proj_fwd(c, Ysa, None, Wsa, None)
     np.testing.assert_allclose(single, orc.gate_proj_fwd(c, Ysa, np.zeros_like(Ysa), Wsa, Wswa), atol=1e-15)
+
+
+def test_gate_projection_backward_against_autograd_and_finite_differences():
+    B, H, n, d = 2, 2, 5, 4
+    dm = H * d
+    c = orc.desc(B, H, H, n, d, 4)
+    Ysa, Yswa, dY = rnd((B, H, n, d), 311), rnd((B, H, n, d), 312), rnd((B, H, n, d), 313)
+    Wsa, Wswa = rnd((dm, dm), 314) * 0.6, rnd((dm, dm), 315) * 0.6
+    got = orc.gate_proj_bwd(c, Ysa, Yswa, Wsa, Wswa, dY)
+    # library autograd on the token-major form
+    t = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
+         for k, v in dict(Ysa=Ysa, Yswa=Yswa, Wsa=Wsa, Wswa=Wswa).items()}
+    tok = lambda Y: Y.permute(0, 2, 1, 3).reshape(B, n, dm)
+    ya, yb = tok(t["Ysa"]), tok(t["Yswa"])
+    Yt = torch.sigmoid(ya @ t["Wsa"].T) * ya + torch.sigmoid(yb @ t["Wswa"].T) * yb
+    (Yt * tok(torch.tensor(dY))).sum().backward()
+    for k, name in (("Ysa", "dYsa"), ("Yswa", "dYswa"), ("Wsa", "dWsa"), ("Wswa", "dWswa")):
+        np.testing.assert_allclose(got[name], t[k].grad.numpy(), rtol=1e-11, atol=1e-12, err_msg=name)
+    # central finite differences of <Y, dY> on a few entries of every argument (forward oracle only)
+    f = lambda a, b_, wa, wb: float((orc.gate_proj_fwd(c, a, b_, wa, wb) * dY).sum())
+    eps = 1e-6
+    for name, arr, pos in (("dYsa", Ysa, (1, 0, 3, 2)), ("dYswa", Yswa, (0, 1, 4, 1)),
+                           ("dWsa", Wsa, (3, 6)), ("dWswa", Wswa, (7, 0))):
+        args = dict(a=Ysa.copy(), b_=Yswa.copy(), wa=Wsa.copy(), wb=Wswa.copy())
+        key = {"dYsa": "a", "dYswa": "b_", "dWsa": "wa", "dWswa": "wb"}[name]
+        args[key][pos] += eps
+        up = f(**args)
+        args[key][pos] -= 2 * eps
+        dn = f(**args)
+        assert abs((up - dn) / (2 * eps) - got[name][pos]) < 1e-7 * max(1.0, abs(got[name][pos])), name
+    # single path: same formulas with one branch
+    one = orc.gate_proj_bwd(c, Ysa, None, Wsa, None, dY)
+    np.testing.assert_allclose(one["dYsa"], got["dYsa"], atol=1e-15)
+    np.testing.assert_allclose(one["dWsa"], got["dWsa"], atol=1e-15)
