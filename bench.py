@@ -125,13 +125,20 @@ def training_ops(sa, synth, dev, reps):
     # the gate projections of the paper's layer (Eq. 6 + Eq. 5) on the two branch outputs, d_model = H*d
     dm = H * d
     Wsa, Wswa = (rn((dm, dm), torch.float32).mul_(dm ** -0.5).to(torch.bfloat16) for _ in range(2))
-    _, t_gp = time_op(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y), reps, 2)
+    Gsa, Gswa, dYsa, dYswa = (torch.empty_like(Q) for _ in range(4))
+    dWsa, dWswa = torch.empty_like(Wsa), torch.empty_like(Wswa)
+    wsg = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATE_PROJ_BWD), device=dev, dtype=torch.uint8)
+    _, t_gp = time_op(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
+    _, t_gpb = time_op(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
+                                                   dWsa, dWswa, wsg), reps, 2)
+    del Gsa, Gswa, dYsa, dYswa, wsg
     flop_gp = 2 * 2.0 * B * n * dm * dm
     W = band_slots(n, w, 0)
     flop_fb = 14.0 * n * W * d * B * H  # forward 4, backward 10 per (query, in-window slot, d)
     return {"pretrain_8k": {
         "gate_proj_fwd_ms": t_gp, "gate_proj_fwd_tflops": flop_gp / (t_gp * 1e-3) / 1e12,
         "gate_proj_fwd_frac_mfma_peak": flop_gp / (t_gp * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "gate_proj_bwd_ms": t_gpb, "gate_proj_bwd_tflops": 2 * flop_gp / (t_gpb * 1e-3) / 1e12,
         "shape": "B4 H16 n8192 d64 w256 bf16",
         "sa_fwd_ms": t_fwd, "sa_bwd_ms": t_bwd,
         "sa_fwdbwd_tokens_per_s": B * n / ((t_fwd + t_bwd) * 1e-3),

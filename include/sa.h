@@ -71,7 +71,10 @@ typedef struct {
 } sa_desc;
 
 typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BWD = 3,
-               SA_OP_CHECK_PERM = 4 } sa_op;
+               SA_OP_CHECK_PERM = 4,
+               SA_OP_GATE_PROJ_BWD = 5,        /* sa_gate_proj_bwd, both branches */
+               SA_OP_GATE_PROJ_BWD_SINGLE = 6  /* sa_gate_proj_bwd, single path   */
+} sa_op;
 
 const char* sa_status_string(sa_status s);
 
@@ -110,6 +113,19 @@ sa_status sa_permuted_copy(const sa_desc* desc, const void* Q, const void* K, co
  * of the descriptor only B, Hq, n, d and dtype are used.  No workspace. */
 sa_status sa_gate_proj_fwd(const sa_desc* desc, const void* Y_sa, const void* Y_swa, const void* W_sa,
                            const void* W_swa, void* Y, void* G_sa, void* G_swa, void* stream);
+
+/* Backward of sa_gate_proj_fwd.  With g_x the gate values the forward wrote (G_sa, G_swa) and dY the
+ * gradient with respect to Y:
+ *   dz_x = dY * y_x * g_x * (1 - g_x),   dY_x[t] = dY[t] * g_x[t] + W_x^T dz_x[t],   dW_x = sum_t dz_x[t] y_x[t]^T
+ * dY_sa, dY_swa: [B,Hq,n,d]; dW_sa, dW_swa: [dm, dm] like the weights; all overwritten.  The *_swa
+ * arguments are all NULL for the single path.  ws: sa_workspace_bytes(desc, SA_OP_GATE_PROJ_BWD or
+ * SA_OP_GATE_PROJ_BWD_SINGLE) bytes.  dz_x is rounded to the tensor dtype before the two products;
+ * dW_x is accumulated in fp32 (order of the additions not fixed) and rounded once.  Same support as
+ * the forward. */
+sa_status sa_gate_proj_bwd(const sa_desc* desc, const void* Y_sa, const void* Y_swa, const void* W_sa,
+                           const void* W_swa, const void* G_sa, const void* G_swa, const void* dY,
+                           void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
+                           void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,

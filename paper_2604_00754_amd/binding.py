@@ -15,9 +15,11 @@ SA_OK, SA_ERR_NULL, SA_ERR_SHAPE, SA_ERR_UNSUPPORTED, SA_ERR_WORKSPACE, SA_ERR_B
 SA_BF16, SA_F32 = 0, 1
 SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
+SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE = 5, 6
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
-           "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd")
+           "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
+           "sa_gate_proj_bwd")
 
 
 class sa_desc(C.Structure):
@@ -53,6 +55,8 @@ def _load():
     lib.sa_permuted_copy.argtypes = [dp, vp, vp, vp, ip, vp, vp]
     lib.sa_gate_proj_fwd.restype = C.c_int
     lib.sa_gate_proj_fwd.argtypes = [dp] + [vp] * 8
+    lib.sa_gate_proj_bwd.restype = C.c_int
+    lib.sa_gate_proj_bwd.argtypes = [dp] + [vp] * 12 + [sz, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -113,6 +117,13 @@ def sa_permuted_copy(desc, Q, K, V, perm, Y):
 def sa_gate_proj_fwd(desc, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa=None, G_swa=None):
     _check(_lib.sa_gate_proj_fwd(C.byref(desc), _ptr(Y_sa), _ptr(Y_swa), _ptr(W_sa), _ptr(W_swa), _ptr(Y),
                                  _ptr(G_sa), _ptr(G_swa), _stream()), "sa_gate_proj_fwd")
+
+
+def sa_gate_proj_bwd(desc, Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa, dY, dY_sa, dY_swa, dW_sa, dW_swa, ws):
+    _check(_lib.sa_gate_proj_bwd(C.byref(desc), _ptr(Y_sa), _ptr(Y_swa), _ptr(W_sa), _ptr(W_swa), _ptr(G_sa),
+                                 _ptr(G_swa), _ptr(dY), _ptr(dY_sa), _ptr(dY_swa), _ptr(dW_sa), _ptr(dW_swa),
+                                 _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
+                                 _stream()), "sa_gate_proj_bwd")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

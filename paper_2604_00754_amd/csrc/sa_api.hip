@@ -134,6 +134,8 @@ size_t sa_workspace_bytes(const sa_desc* c, int op) {
     case SA_OP_BWD: return bwd_workspace(c, false).total;
     case SA_OP_GATED_BWD: return bwd_workspace(c, true).total;
     case SA_OP_CHECK_PERM: return align256((size_t)c->perm_B * c->perm_H * c->n * sizeof(int)) + 256;
+    case SA_OP_GATE_PROJ_BWD: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, true);
+    case SA_OP_GATE_PROJ_BWD_SINGLE: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, false);
     default: return 0;
   }
 }
@@ -190,6 +192,25 @@ sa_status sa_gate_proj_fwd(const sa_desc* c, const void* Y_sa, const void* Y_swa
   if (((long)c->Hq * c->d) % 128 != 0) return SA_ERR_UNSUPPORTED;  // whole 128-feature tiles
   return hip_status(sa::launch_gate_proj_fwd_bf16(c->B, c->Hq, c->n, c->d, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa,
                                                   G_swa, (hipStream_t)stream));
+}
+
+sa_status sa_gate_proj_bwd(const sa_desc* c, const void* Y_sa, const void* Y_swa, const void* W_sa,
+                           const void* W_swa, const void* G_sa, const void* G_swa, const void* dY,
+                           void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa, void* ws, size_t ws_bytes,
+                           void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Y_sa || !W_sa || !G_sa || !dY || !dY_sa || !dW_sa) return SA_ERR_NULL;
+  const bool dual = Y_swa != nullptr;
+  if (dual != (W_swa != nullptr) || dual != (G_swa != nullptr) || dual != (dY_swa != nullptr) ||
+      dual != (dW_swa != nullptr))
+    return SA_ERR_NULL;
+  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  if (((long)c->Hq * c->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
+  const size_t need = sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, dual);
+  if (!ws || ws_bytes < need) return SA_ERR_WORKSPACE;
+  return hip_status(sa::launch_gate_proj_bwd_bf16(c->B, c->Hq, c->n, c->d, Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa, dY,
+                                                  dY_sa, dY_swa, dW_sa, dW_swa, ws, (hipStream_t)stream));
 }
 
 sa_status swa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, void* Y, float* LSE,

@@ -65,6 +65,12 @@ hipError_t launch_gate_proj_fwd_bf16(int B, int Hq, int n, int d, const void* Y_
                                      const void* W_sa, const void* W_swa, void* Y, void* G_sa, void* G_swa,
                                      hipStream_t st);
 
+size_t gate_proj_bwd_workspace_bytes(int B, int Hq, int n, int d, bool dual);
+hipError_t launch_gate_proj_bwd_bf16(int B, int Hq, int n, int d, const void* Y_sa, const void* Y_swa,
+                                     const void* W_sa, const void* W_swa, const void* G_sa, const void* G_swa,
+                                     const void* dY, void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
+                                     void* ws, hipStream_t st);
+
 // helpers in sa_misc.hip
 hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag,
                              hipStream_t st);

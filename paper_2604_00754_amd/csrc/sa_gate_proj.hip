@@ -13,6 +13,15 @@
 // is formed transposed (A operand = weight rows, B operand = token rows): a lane then owns one
 // token and each accumulator quad four consecutive output features, i.e. 8 contiguous bytes of
 // Y_x and Y.
+//
+// Backward (given dY; g_x saved by the forward):
+//   dz_x = dY * y_x * g_x * (1 - g_x)                     element-wise pass, rounded to bf16
+//   dy_x = dY * g_x + W_x^T dz_x                          the forward kernel again: tokens = dz_x,
+//                                                         weights = W_x^T (transposed once), epilogue = + dY * g_x
+//   dW_x = sum_t dz_x[t] y_x[t]^T                         contraction over tokens: both operands are
+//                                                         transposed on their way into LDS (4 x 8 register
+//                                                         transposes), a workgroup owns 128 x 128 of dW for a
+//                                                         chunk of tokens and adds it with fp32 atomics
 #include "sa_common.h"
 #include "sa_mfma.h"
 
@@ -32,10 +41,14 @@ struct GateProj {
   const void* W_x[2];  // [dm, dm] row-major, row = output feature
   void* G_x[2];        // optional: gate values sigmoid(logit) [B,Hq,n,d]
   void* Y;             // [B,Hq,n,d]
+  const void* E1;      // backward-input mode: Y = acc + E1 * E2 (E1 = dY, E2 = g_x), both [B,Hq,n,d]
+  const void* E2;
   int B, Hq, n, d;
 };
 
-template <int D>
+enum { GP_FORWARD = 0, GP_BWD_INPUT = 1 };
+
+template <int D, int MODE>
 __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GateProj p, const int num_tt, const int num_ft,
                                                                     const long total_work) {
   __shared__ __attribute__((aligned(16))) char smem[2 * GBUF_BYTES];
@@ -130,7 +143,10 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
     }
 
     // Eq. 6 / Eq. 5 for this branch: out += sigmoid(logit) * Y_x at the same (token, feature)
+    // (backward-input mode: out = product + dY * g_x)
     bf16_t* Gx = reinterpret_cast<bf16_t*>(p.G_x[x]);
+    const bf16_t* E1 = reinterpret_cast<const bf16_t*>(p.E1);
+    const bf16_t* E2 = reinterpret_cast<const bf16_t*>(p.E2);
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       const int token = i0 + 64 * wm + 32 * ti + c32;
@@ -142,19 +158,27 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
         for (int q = 0; q < 4; ++q) {
           const int o = o0 + 64 * wn + 32 * fi + 8 * q + 4 * g2;  // first of four consecutive features
           const size_t at = (((size_t)b * H + o / D) * n + tk) * D + o % D;
-          const u32x2 y = *reinterpret_cast<const u32x2*>(Yx + at);
-          const float yv[4] = {bf16lo(y[0]), bf16hi(y[0]), bf16lo(y[1]), bf16hi(y[1])};
-          float gv[4];
+          if (MODE == GP_FORWARD) {
+            const u32x2 y = *reinterpret_cast<const u32x2*>(Yx + at);
+            const float yv[4] = {bf16lo(y[0]), bf16hi(y[0]), bf16lo(y[1]), bf16hi(y[1])};
+            float gv[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            gv[e] = sigmoidf_exact(acc[fi][ti][4 * q + e]);
-            out[fi][ti][4 * q + e] = fmaf(gv[e], yv[e], out[fi][ti][4 * q + e]);
-          }
-          if (Gx && live) {
-            u32x2 w;
-            w[0] = pack_bf16(gv[0], gv[1]);
-            w[1] = pack_bf16(gv[2], gv[3]);
-            *reinterpret_cast<u32x2*>(Gx + at) = w;
+            for (int e = 0; e < 4; ++e) {
+              gv[e] = sigmoidf_exact(acc[fi][ti][4 * q + e]);
+              out[fi][ti][4 * q + e] = fmaf(gv[e], yv[e], out[fi][ti][4 * q + e]);
+            }
+            if (Gx && live) {
+              u32x2 w;
+              w[0] = pack_bf16(gv[0], gv[1]);
+              w[1] = pack_bf16(gv[2], gv[3]);
+              *reinterpret_cast<u32x2*>(Gx + at) = w;
+            }
+          } else {
+            const u32x2 a = *reinterpret_cast<const u32x2*>(E1 + at), c = *reinterpret_cast<const u32x2*>(E2 + at);
+            out[fi][ti][4 * q + 0] = fmaf(bf16lo(a[0]), bf16lo(c[0]), acc[fi][ti][4 * q + 0]);
+            out[fi][ti][4 * q + 1] = fmaf(bf16hi(a[0]), bf16hi(c[0]), acc[fi][ti][4 * q + 1]);
+            out[fi][ti][4 * q + 2] = fmaf(bf16lo(a[1]), bf16lo(c[1]), acc[fi][ti][4 * q + 2]);
+            out[fi][ti][4 * q + 3] = fmaf(bf16hi(a[1]), bf16hi(c[1]), acc[fi][ti][4 * q + 3]);
           }
         }
     }
@@ -179,6 +203,165 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
   }
 }
 
+
+// dz = dY * y * g * (1 - g), rounded to bf16; 8 elements per thread.
+__global__ __launch_bounds__(256) void gate_dz_bf16_kernel(const uint16_t* __restrict__ dY, const uint16_t* __restrict__ Yx,
+                                                            const uint16_t* __restrict__ Gx, uint16_t* __restrict__ dz,
+                                                            const size_t vecs) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < vecs; i += stride) {
+    const u32x4 a = *reinterpret_cast<const u32x4*>(dY + 8 * i), y = *reinterpret_cast<const u32x4*>(Yx + 8 * i);
+    const u32x4 g = *reinterpret_cast<const u32x4*>(Gx + 8 * i);
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float gl = bf16lo(g[e]), gh = bf16hi(g[e]);
+      o[e] = pack_bf16(bf16lo(a[e]) * bf16lo(y[e]) * gl * (1.f - gl), bf16hi(a[e]) * bf16hi(y[e]) * gh * (1.f - gh));
+    }
+    *reinterpret_cast<u32x4*>(dz + 8 * i) = o;
+  }
+}
+
+// Wt[k][o] = W[o][k] for a square bf16 matrix (dm a multiple of 64): 64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ Wt, const int dm) {
+  __shared__ uint16_t tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) tile[e / 64][e % 64] = W[(size_t)(r0 + e / 64) * dm + c0 + e % 64];
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * 64; e += 256) Wt[(size_t)(c0 + e / 64) * dm + r0 + e % 64] = tile[e % 64][e / 64];
+}
+
+// dW[o][k] += sum over a chunk of tokens of dz[t][o] * y[t][k].  Workgroup = 128 x 128 of dW, 4 waves
+// as 2 x 2, token step 64; both tiles are stored transposed ([feature][token], +16 B padding) so that
+// the token index is the contiguous one for the matrix instructions.  Tokens past n contribute zeros.
+constexpr int WCHUNK = 4096;  // tokens per workgroup
+constexpr int WSTEP = 64;
+constexpr int WSTR = WSTEP + 8;
+constexpr int WTILE_BYTES = 128 * WSTR * 2;
+
+template <int D>
+__global__ __launch_bounds__(GNT, 2) void gate_dw_bf16_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ Yx,
+                                                               float* __restrict__ dW, const int B, const int H, const int n,
+                                                               const int num_ft, const int chunks_per_b, const long total_work) {
+  __shared__ __attribute__((aligned(16))) char smem[2 * 2 * WTILE_BYTES];
+  const long work = xcd_work_index(total_work);
+  if (work < 0) return;
+  const int kt = (int)(work % num_ft);  // input-feature tile (columns of dW)
+  long rest = work / num_ft;
+  const int ot = (int)(rest % num_ft);  // output-feature tile (rows of dW)
+  rest /= num_ft;
+  const int ch = (int)(rest % chunks_per_b);
+  const int b = (int)(rest / chunks_per_b);
+  const int dm = H * D;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = wave & 1, wk = wave >> 1;
+  const int g2 = lane >> 5, c32 = lane & 31;
+  const int t_begin = ch * WCHUNK, t_end = min(t_begin + WCHUNK, n);
+  const int nsteps = (t_end - t_begin + WSTEP - 1) / WSTEP;
+
+  // loader unit: tokens 4u..4u+3 (u = tid % 16) x 16-byte feature chunk tid / 16 (16 chunks = 128 features)
+  const int lu = tid & 15, lc = tid >> 4;
+  auto feat_base = [&](const bf16_t* X, int f0) -> const bf16_t* {  // row 0 of feature chunk lc of tile f0
+    const int f = f0 + lc * 8;
+    return X + ((size_t)b * H + f / D) * n * (size_t)D + f % D;
+  };
+  const bf16_t* zbase = feat_base(dz, ot * 128);
+  const bf16_t* ybase = feat_base(Yx, kt * 128);
+  u32x4 zreg[4], yreg[4];
+  auto load_step = [&](int st) {
+    const int t0 = t_begin + st * WSTEP + 4 * lu;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = t0 + j;
+      const bool live = t < t_end;
+      const size_t row = (size_t)(live ? t : t_end - 1) * D;
+      zreg[j] = *reinterpret_cast<const u32x4*>(zbase + row);
+      yreg[j] = *reinterpret_cast<const u32x4*>(ybase + row);
+      if (!live) { zreg[j] = u32x4{0u, 0u, 0u, 0u}; yreg[j] = u32x4{0u, 0u, 0u, 0u}; }
+    }
+  };
+  auto store_step = [&](int buf) {
+    bf16_t* Zt = reinterpret_cast<bf16_t*>(smem + buf * 2 * WTILE_BYTES);
+    bf16_t* Yt = reinterpret_cast<bf16_t*>(smem + buf * 2 * WTILE_BYTES + WTILE_BYTES);
+    store_transposed_4x8(Zt + (8 * lc) * WSTR + 4 * lu, WSTR, zreg);
+    store_transposed_4x8(Yt + (8 * lc) * WSTR + 4 * lu, WSTR, yreg);
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int oi = 0; oi < 2; ++oi)
+#pragma unroll
+    for (int ki = 0; ki < 2; ++ki)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[oi][ki][i] = 0.f;
+
+  load_step(0);
+  store_step(0);
+  if (nsteps > 1) load_step(1);
+  for (int st = 0; st < nsteps; ++st) {
+    const int buf = st & 1;
+    __syncthreads();
+    if (st + 1 < nsteps) {
+      store_step(buf ^ 1);
+      if (st + 2 < nsteps) load_step(st + 2);
+    }
+    const bf16_t* Zt = reinterpret_cast<const bf16_t*>(smem + buf * 2 * WTILE_BYTES) + (64 * wo + c32) * WSTR + 8 * g2;
+    const bf16_t* Yt = reinterpret_cast<const bf16_t*>(smem + buf * 2 * WTILE_BYTES + WTILE_BYTES) + (64 * wk + c32) * WSTR + 8 * g2;
+#pragma unroll
+    for (int ks = 0; ks < WSTEP / 16; ++ks) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int oi = 0; oi < 2; ++oi) fa[oi] = *reinterpret_cast<const bf16x8*>(Zt + 32 * oi * WSTR + 16 * ks);
+#pragma unroll
+      for (int ki = 0; ki < 2; ++ki) fb[ki] = *reinterpret_cast<const bf16x8*>(Yt + 32 * ki * WSTR + 16 * ks);
+#pragma unroll
+      for (int oi = 0; oi < 2; ++oi)
+#pragma unroll
+        for (int ki = 0; ki < 2; ++ki) acc[oi][ki] = mfma_bf16(fa[oi], fb[ki], acc[oi][ki]);
+    }
+  }
+  // accumulator 4q + x of lane (g2, c32): row o = 64wo + 32oi + 8q + 4g2 + x, column k = 64wk + 32ki + c32
+#pragma unroll
+  for (int oi = 0; oi < 2; ++oi)
+#pragma unroll
+    for (int ki = 0; ki < 2; ++ki)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int o = ot * 128 + 64 * wo + 32 * oi + 8 * (i / 4) + 4 * g2 + (i % 4);
+        const int k = kt * 128 + 64 * wk + 32 * ki + c32;
+        unsafeAtomicAdd(dW + (size_t)o * dm + k, acc[oi][ki][i]);  // hardware fp32 add, device memory
+      }
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, const size_t pairs) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < pairs; i += stride) {
+    const f32x2 v = *reinterpret_cast<const f32x2*>(src + 2 * i);
+    *reinterpret_cast<uint32_t*>(dst + 2 * i) = pack_bf16(v[0], v[1]);
+  }
+}
+
+template <int MODE>
+hipError_t launch_gemm(const GateProj& p, hipStream_t st) {
+  const long dm = (long)p.Hq * p.d;
+  const int num_tt = (p.n + TM - 1) / TM, num_ft = (int)(dm / TN);
+  const long total = (long)num_tt * num_ft * p.B;
+  const long blocks = xcd_grid_blocks(total);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  if (p.d == 64) hipLaunchKernelGGL((gate_proj_fwd_bf16_kernel<64, MODE>), dim3((unsigned)blocks), dim3(GNT), 0, st, p, num_tt, num_ft, total);
+  else hipLaunchKernelGGL((gate_proj_fwd_bf16_kernel<128, MODE>), dim3((unsigned)blocks), dim3(GNT), 0, st, p, num_tt, num_ft, total);
+  return hipGetLastError();
+}
+
+unsigned capped_blocks(size_t items, size_t per_block) {
+  const size_t want = (items + per_block - 1) / per_block;
+  return (unsigned)(want < 1 ? 1 : (want > 65536 ? 65536 : want));
+}
+
 }  // namespace
 
 hipError_t launch_gate_proj_fwd_bf16(int B, int Hq, int n, int d, const void* Y_sa, const void* Y_swa, const void* W_sa,
@@ -194,13 +377,69 @@ hipError_t launch_gate_proj_fwd_bf16(int B, int Hq, int n, int d, const void* Y_
   p.G_x[0] = G_sa; p.G_x[1] = G_swa;
   p.Y = Y;
   p.B = B; p.Hq = Hq; p.n = n; p.d = d;
-  const int num_tt = (n + TM - 1) / TM, num_ft = (int)(dm / TN);
-  const long total = (long)num_tt * num_ft * B;
+  return launch_gemm<GP_FORWARD>(p, st);
+}
+
+size_t gate_proj_bwd_workspace_bytes(int B, int Hq, int n, int d, bool dual) {
+  const size_t dm = (size_t)Hq * d, act = (size_t)B * Hq * n * d;
+  const size_t per_branch = act * 2 /* dz bf16 */ + dm * dm * 2 /* W^T bf16 */ + dm * dm * 4 /* dW fp32 */;
+  return (dual ? 2 : 1) * ((per_branch + 255) / 256 * 256);
+}
+
+// One branch: dz, W^T, dy_x = dY * g_x + dz W_x, dW_x = dz^T y_x.
+static hipError_t gate_proj_bwd_branch(int B, int Hq, int n, int d, const void* Yx, const void* Wx, const void* Gx,
+                                       const void* dY, void* dYx, void* dWx, char* ws, hipStream_t st) {
+  const size_t dm = (size_t)Hq * d, act = (size_t)B * Hq * n * d;
+  uint16_t* dz = reinterpret_cast<uint16_t*>(ws);
+  uint16_t* Wt = reinterpret_cast<uint16_t*>(ws + act * 2);
+  float* dWf = reinterpret_cast<float*>(ws + act * 2 + dm * dm * 2);
+  hipLaunchKernelGGL(gate_dz_bf16_kernel, dim3(capped_blocks(act / 8, 256)), dim3(256), 0, st,
+                     reinterpret_cast<const uint16_t*>(dY), reinterpret_cast<const uint16_t*>(Yx),
+                     reinterpret_cast<const uint16_t*>(Gx), dz, act / 8);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)(dm / 64), (unsigned)(dm / 64)), dim3(256), 0, st,
+                     reinterpret_cast<const uint16_t*>(Wx), Wt, (int)dm);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  GateProj p = {};
+  p.Y_x[0] = dz; p.W_x[0] = Wt;
+  p.Y = dYx; p.E1 = dY; p.E2 = Gx;
+  p.B = B; p.Hq = Hq; p.n = n; p.d = d;
+  e = launch_gemm<GP_BWD_INPUT>(p, st);
+  if (e != hipSuccess) return e;
+  e = launch_fill_zero(dWf, dm * dm * 4, st);
+  if (e != hipSuccess) return e;
+  const int num_ft = (int)(dm / 128), chunks = (n + WCHUNK - 1) / WCHUNK;
+  const long total = (long)num_ft * num_ft * chunks * B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  if (d == 64) hipLaunchKernelGGL(gate_proj_fwd_bf16_kernel<64>, dim3((unsigned)blocks), dim3(GNT), 0, st, p, num_tt, num_ft, total);
-  else hipLaunchKernelGGL(gate_proj_fwd_bf16_kernel<128>, dim3((unsigned)blocks), dim3(GNT), 0, st, p, num_tt, num_ft, total);
+  if (d == 64) hipLaunchKernelGGL(gate_dw_bf16_kernel<64>, dim3((unsigned)blocks), dim3(GNT), 0, st, reinterpret_cast<const bf16_t*>(dz),
+                                  reinterpret_cast<const bf16_t*>(Yx), dWf, B, Hq, n, num_ft, chunks, total);
+  else hipLaunchKernelGGL(gate_dw_bf16_kernel<128>, dim3((unsigned)blocks), dim3(GNT), 0, st, reinterpret_cast<const bf16_t*>(dz),
+                          reinterpret_cast<const bf16_t*>(Yx), dWf, B, Hq, n, num_ft, chunks, total);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(capped_blocks(dm * dm / 2, 256)), dim3(256), 0, st, dWf,
+                     reinterpret_cast<uint16_t*>(dWx), dm * dm / 2);
   return hipGetLastError();
+}
+
+hipError_t launch_gate_proj_bwd_bf16(int B, int Hq, int n, int d, const void* Y_sa, const void* Y_swa, const void* W_sa,
+                                     const void* W_swa, const void* G_sa, const void* G_swa, const void* dY, void* dY_sa,
+                                     void* dY_swa, void* dW_sa, void* dW_swa, void* ws, hipStream_t st) {
+  if (B < 1 || Hq < 1 || n < 1 || !Y_sa || !W_sa || !G_sa || !dY || !dY_sa || !dW_sa || !ws) return hipErrorInvalidValue;
+  const bool dual = Y_swa != nullptr;
+  if (dual != (W_swa != nullptr) || dual != (G_swa != nullptr) || dual != (dY_swa != nullptr) || dual != (dW_swa != nullptr))
+    return hipErrorInvalidValue;
+  if (!(d == 64 || d == 128)) return hipErrorNotSupported;
+  const long dm = (long)Hq * d;
+  if (dm % 128 != 0) return hipErrorNotSupported;
+  char* base = reinterpret_cast<char*>(ws);
+  hipError_t e = gate_proj_bwd_branch(B, Hq, n, d, Y_sa, W_sa, G_sa, dY, dY_sa, dW_sa, base, st);
+  if (e != hipSuccess || !dual) return e;
+  const size_t half = gate_proj_bwd_workspace_bytes(B, Hq, n, d, false);
+  return gate_proj_bwd_branch(B, Hq, n, d, Y_swa, W_swa, G_swa, dY, dY_swa, dW_swa, base + half, st);
 }
 
 }  // namespace sa

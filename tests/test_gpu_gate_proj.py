@@ -75,3 +75,51 @@ def test_gate_proj_rejects_unsupported():
         w2 = torch.zeros((128, 128), device=U.DEV, dtype=torch.bfloat16)
         sa.sa_gate_proj_fwd(sa.make_desc(1, 2, 2, 8, 64, 4), t2, t2, w2, None, torch.empty_like(t2))
     assert e.value.status == sa.SA_ERR_NULL
+
+
+def run_bwd_case(B, H, n, d, seed, dual=True):
+    """Forward on the GPU (to get the gate values it saves), then the backward, against the fp64
+    gradient of the oracle.  The oracle recomputes g_x in fp64; the GPU uses its bf16-rounded copy."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    dm = H * d
+    print(f"case gate_proj_bwd B{B} H{H} n{n} d{d} dm{dm} dual={dual}", flush=True)
+    rng = np.random.default_rng(synth.BASE_SEED + 100 + seed)
+    r16 = lambda a: synth.round_to_bf16(a.astype(np.float32))
+    Ysa, Yswa, dY = (r16(rng.standard_normal((B, H, n, d))) for _ in range(3))
+    Wsa, Wswa = (r16(rng.standard_normal((dm, dm)) / np.sqrt(dm)) for _ in range(2))
+    c = orc.desc(B, H, H, n, d, 4)
+    ref = orc.gate_proj_bwd(c, Ysa, Yswa if dual else None, Wsa, Wswa if dual else None, dY)
+    dev = lambda a: U.to_dev(a, "bf16")
+    tYsa, tWsa, tdY = dev(Ysa), dev(Wsa), dev(dY)
+    tYswa, tWswa = (dev(Yswa), dev(Wswa)) if dual else (None, None)
+    Y, Ga = torch.empty_like(tYsa), torch.empty_like(tYsa)
+    Gb = torch.empty_like(tYsa) if dual else None
+    desc = sa.make_desc(B, H, H, n, d, 4)
+    sa.sa_gate_proj_fwd(desc, tYsa, tYswa, tWsa, tWswa, Y, Ga, Gb)
+    nan = lambda t: torch.full_like(t, float("nan"))
+    dYsa, dWsa = nan(tYsa), nan(tWsa)
+    dYswa, dWswa = (nan(tYsa), nan(tWsa)) if dual else (None, None)
+    op = sa.SA_OP_GATE_PROJ_BWD if dual else sa.SA_OP_GATE_PROJ_BWD_SINGLE
+    ws = torch.empty(sa.sa_workspace_bytes(desc, op), device=U.DEV, dtype=torch.uint8)
+    sa.sa_gate_proj_bwd(desc, tYsa, tYswa, tWsa, tWswa, Ga, Gb, tdY, dYsa, dYswa, dWsa, dWswa, ws)
+    torch.cuda.synchronize()
+    # gradients are sums of bf16-rounded products: max-abs bar scaled by the tensor's own magnitude
+    for name, got in (("dYsa", dYsa), ("dWsa", dWsa)) + ((("dYswa", dYswa), ("dWswa", dWswa)) if dual else ()):
+        r = ref[name]
+        U.assert_close(U.to_np64(got), r, "bf16", name, scale_abs=max(1.0, float(np.abs(r).max())))
+    if not dual:  # too small a workspace is refused on the host
+        with pytest.raises(sa.SaError) as e:
+            sa.sa_gate_proj_bwd(desc, tYsa, None, tWsa, None, Ga, None, tdY, dYsa, None, dWsa, None, ws[:-256])
+        assert e.value.status == sa.SA_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("d,H", [(64, 2), (64, 4), (128, 1), (128, 2)])
+def test_gate_proj_bwd_dual_path(d, H):
+    run_bwd_case(2, H, 300, d, seed=d + H)
+
+
+def test_gate_proj_bwd_single_path_and_several_token_chunks():
+    run_bwd_case(1, 2, 9000, 64, seed=5, dual=False)   # 3 token chunks of the dW kernel, ragged tail
+    run_bwd_case(2, 2, 1100, 64, seed=6, dual=True)
