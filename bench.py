@@ -321,6 +321,13 @@ def main():
                 cold.append(a.elapsed_time(b))
             other["cold_cache_ms"] = float(np.median(cold))
             del cs, cd
+        # on-device permutation sampling (one layer, one permutation shared by the heads)
+        sampled = torch.empty((1, 1, wl.n), device=dev, dtype=torch.int32)
+        _, sp_ms = time_op(lambda: sa.sa_sample_perm(desc, 1, 0, sampled), 10, 2)
+        d8k = sa.make_desc(4, 16, 16, 8192, 64, 256)
+        sampled8k = torch.empty((1, 1, 8192), device=dev, dtype=torch.int32)
+        _, sp8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k), 10, 2)
+        other.update({"sample_perm_n32768_ms": sp_ms, "sample_perm_n8192_ms": sp8_ms})
         del Y2
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
         other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))

@@ -92,6 +92,18 @@ sa_status sa_check_perm(const sa_desc* desc, const int32_t* perm, void* ws, size
 sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                  const int32_t* perm, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
 
+/* Samples the permutations of one layer on the device (Sec. 3.3 and App. A: sigma ~ Uniform(S_n),
+ * drawn independently per layer, fresh at every step if the caller changes `seed`).  Writes perm
+ * [perm_B, perm_H, n] in the convention of this header (perm[..., p] = original index of the token at
+ * slot p).  Method: sort by random key.  Slice s = pb*perm_H + ph uses the SplitMix64 sequence
+ *   stream = mix(mix(seed) + G*((layer << 32) | s)),  r(p) = mix(stream + G*(p+1)),  G = 0x9E3779B97F4A7C15,
+ * mix = the SplitMix64 output function; the sort key of slot p is r(p) with its low 20 bits replaced
+ * by p (44 random bits, ties - probability < n^2/2^45 per slice - go to the smaller p), and perm = the
+ * argsort of the keys.  Deterministic in (seed, layer, slice, n); O(n^2) compares per slice, no
+ * workspace, no host round trip.  layer >= 0; n <= 2^20 (SA_ERR_UNSUPPORTED beyond); at most 65535
+ * slices. */
+sa_status sa_sample_perm(const sa_desc* desc, uint64_t seed, int32_t layer, int32_t* perm, void* stream);
+
 /* Measurement helper: the gather and the scatter of Alg. 1 (Sec. 3.3, the two index operations around
  * the attention) with no attention in between.  For every (b, hq, slot p), with i = perm[p]:
  *   Y[b,hq,i,:] = Q[b,hq,i,:]                                   if hq is not the first head of its KV group

@@ -6,12 +6,13 @@ element).  The sampler is "sort by random key": slot p of slice (pb, ph) of laye
 64-bit key
 
     stream = mix(mix(seed) + GAMMA * ((layer << 32) | slice)),   slice = pb * perm_H + ph
-    key(p) = mix(stream + GAMMA * (p + 1))
+    r(p)   = mix(stream + GAMMA * (p + 1))
 
-i.e. the (p+1)-th output of the SplitMix64 generator (Steele, Lea, Flood 2014) started at `stream`;
-perm = the stable argsort of the keys: perm[r] = the p whose key has rank r.  Keys are i.i.d.
-uniform 64-bit values, so the result is uniform over S_n up to key collisions (probability
-< n^2 / 2^65), which the stable sort resolves by index.
+i.e. the (p+1)-th output of the SplitMix64 generator (Steele, Lea, Flood 2014) started at `stream`.
+The sort key is r(p) with its low 20 bits replaced by p (n <= 2^20): 44 i.i.d. uniform bits, ties
+broken by the slot index, all keys distinct.  perm = the argsort of the keys: perm[k] = the p whose
+key has rank k.  The result is uniform over S_n up to collisions of the 44 random bits
+(probability < n^2 / 2^45 per slice).
 """
 import numpy as np
 
@@ -34,6 +35,14 @@ def keys(stream, n):
         return mix(np.uint64(stream) + GAMMA * np.arange(1, n + 1, dtype=np.uint64))
 
 
+INDEX_MASK = np.uint64(0xFFFFF)
+
+
+def sort_keys(stream, n):
+    assert n <= 1 << 20
+    return (keys(stream, n) & ~INDEX_MASK) | np.arange(n, dtype=np.uint64)
+
+
 def stream_of(seed, layer, slice_index):
     with np.errstate(over="ignore"):
         tag = np.uint64((int(layer) << 32) | int(slice_index))
@@ -45,6 +54,6 @@ def sample_perm(seed, layer, perm_B, perm_H, n):
     out = np.empty((perm_B, perm_H, n), np.int32)
     for pb in range(perm_B):
         for ph in range(perm_H):
-            k = keys(stream_of(seed, layer, pb * perm_H + ph), n)
-            out[pb, ph] = np.argsort(k, kind="stable").astype(np.int32)
+            k = sort_keys(stream_of(seed, layer, pb * perm_H + ph), n)
+            out[pb, ph] = np.argsort(k).astype(np.int32)
     return out

@@ -19,7 +19,7 @@ SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE = 5, 6
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
-           "sa_gate_proj_bwd")
+           "sa_gate_proj_bwd", "sa_sample_perm")
 
 
 class sa_desc(C.Structure):
@@ -57,6 +57,8 @@ def _load():
     lib.sa_gate_proj_fwd.argtypes = [dp] + [vp] * 8
     lib.sa_gate_proj_bwd.restype = C.c_int
     lib.sa_gate_proj_bwd.argtypes = [dp] + [vp] * 12 + [sz, vp]
+    lib.sa_sample_perm.restype = C.c_int
+    lib.sa_sample_perm.argtypes = [dp, C.c_uint64, C.c_int32, ip, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -107,6 +109,11 @@ def sa_check_perm(desc, perm, ws):
 def sa_fwd(desc, Q, K, V, perm, Y, LSE=None):
     _check(_lib.sa_fwd(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(Y), _ptr(LSE),
                        None, 0, _stream()), "sa_fwd")
+
+
+def sa_sample_perm(desc, seed, layer, perm):
+    _check(_lib.sa_sample_perm(C.byref(desc), C.c_uint64(int(seed) & (2 ** 64 - 1)), int(layer), _ptr(perm),
+                               _stream()), "sa_sample_perm")
 
 
 def sa_permuted_copy(desc, Q, K, V, perm, Y):

@@ -171,6 +171,15 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   return hip_status(run_fwd(c, p, (hipStream_t)stream));
 }
 
+sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t* perm, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!perm) return SA_ERR_NULL;
+  if (layer < 0) return SA_ERR_SHAPE;
+  if (c->n > (1 << 20)) return SA_ERR_UNSUPPORTED;
+  return hip_status(sa::launch_sample_perm(perm, c->perm_B * c->perm_H, c->n, seed, layer, (hipStream_t)stream));
+}
+
 sa_status sa_permuted_copy(const sa_desc* c, const void* Q, const void* K, const void* V,
                            const int32_t* perm, void* Y, void* stream) {
   sa_status s = validate_desc(c);

@@ -85,6 +85,54 @@ __global__ __launch_bounds__(256) void permuted_copy_bf16_kernel(const Pass p, c
   }
 }
 
+// ---- permutation sampler (Sec. 3.3: sigma ~ Uniform(S_n), fresh per layer): sort by random key.
+// Slot p of slice s gets the 64-bit sort key  (r(p) with its low 20 bits replaced by p),  r(p) = the
+// (p+1)-th output of SplitMix64 started at a per-(seed, layer, slice) stream value: 44 random bits,
+// ties broken by p, all keys distinct.  perm = argsort of the keys, computed as a rank: the thread of
+// slot p counts the keys below its own and writes perm[rank] = p.  All keys of the slice stream
+// through LDS in tiles of 1024; 16 lanes share one slot (each takes every 16th pair of keys of a
+// tile, the partial counts are added with shuffles), so even a short slice fills the chip.
+__device__ __forceinline__ uint64_t splitmix_mix(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t kIndexMask = 0xFFFFFull;  // n <= 2^20
+constexpr int SAMPLE_TILE = 1024;
+
+__device__ __forceinline__ uint64_t sort_key(uint64_t stream, int p) {
+  return (splitmix_mix(stream + kGamma * (uint64_t)(p + 1)) & ~kIndexMask) | (uint64_t)p;
+}
+
+constexpr int SAMPLE_LPP = 16;  // lanes that share the rank count of one slot
+
+__global__ __launch_bounds__(256) void sample_perm_kernel(int32_t* __restrict__ perm, const int n, const uint64_t seed,
+                                                           const int layer) {
+  __shared__ __attribute__((aligned(16))) uint64_t tile[SAMPLE_TILE];
+  const int slice = blockIdx.y;
+  const uint64_t stream = splitmix_mix(splitmix_mix(seed) + kGamma * (((uint64_t)(uint32_t)layer << 32) | (uint32_t)slice));
+  const int p = blockIdx.x * (256 / SAMPLE_LPP) + threadIdx.x / SAMPLE_LPP;
+  const int sub = threadIdx.x % SAMPLE_LPP;
+  const uint64_t mine = sort_key(stream, p);
+  int rank = 0;
+  for (int q0 = 0; q0 < n; q0 += SAMPLE_TILE) {
+    __syncthreads();
+    // keys past the end of the slice are set above every real key
+    for (int j = threadIdx.x; j < SAMPLE_TILE; j += 256) tile[j] = q0 + j < n ? sort_key(stream, q0 + j) : ~0ull;
+    __syncthreads();
+#pragma unroll 8
+    for (int j = 2 * sub; j < SAMPLE_TILE; j += 2 * SAMPLE_LPP) {  // two keys per 16-byte read
+      const ulonglong2 k = *reinterpret_cast<const ulonglong2*>(tile + j);
+      rank += (k.x < mine) ? 1 : 0;
+      rank += (k.y < mine) ? 1 : 0;
+    }
+  }
+#pragma unroll
+  for (int o = SAMPLE_LPP / 2; o > 0; o >>= 1) rank += __shfl_xor(rank, o);
+  if (sub == 0 && p < n) perm[(size_t)slice * n + rank] = p;
+}
+
 template <int LPR>  // lanes per row, each lane owns 16 bytes of the row
 __device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
@@ -224,6 +272,15 @@ hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, 
   if (e != hipSuccess) return e;
   const unsigned blocks = (unsigned)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
   hipLaunchKernelGGL(check_perm_kernel, dim3(blocks), dim3(256), 0, st, perm, total, n, seen, flag);
+  return hipGetLastError();
+}
+
+hipError_t launch_sample_perm(int32_t* perm, int slices, int n, uint64_t seed, int layer, hipStream_t st) {
+  if (!perm || slices < 1 || slices > 65535 || n < 1) return hipErrorInvalidValue;
+  if (n > (1 << 20)) return hipErrorNotSupported;  // the slot index takes the low 20 bits of the sort key
+  const int per_block = 256 / SAMPLE_LPP;
+  hipLaunchKernelGGL(sample_perm_kernel, dim3((unsigned)((n + per_block - 1) / per_block), (unsigned)slices), dim3(256), 0, st,
+                     perm, n, seed, layer);
   return hipGetLastError();
 }
 
