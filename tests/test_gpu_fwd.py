@@ -95,6 +95,14 @@ def test_bf16_long_sequence_uses_32bit_indices():
     run_fwd(1, 1, 1, 66000, 64, 64, CIRC, 1, "bf16", seed=52)
 
 
+@pytest.mark.parametrize("n", [65535, 65536])
+def test_bf16_index_width_boundary(n):
+    """The largest n of the 16-bit causal mode (original positions up to 65534, biased to int16) and the
+    first n of the 32-bit mode."""
+    run_fwd(1, 1, 1, n, 64, 32, CIRC, 1, "bf16", seed=53)
+    run_fwd(1, 1, 1, n, 128, 32, ONE, 1, "bf16", seed=54, identity=True, use_swa_entry=True)
+
+
 def test_pretraining_shape_sample():
     """Second benchmark configuration's shape (B=8,H=12,n=2048,d=64,w=128), SA branch only."""
     run_fwd(8, 12, 12, 2048, 64, 128, CIRC, 1, "bf16", perm_H=12, seed=50)
