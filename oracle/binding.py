@@ -209,3 +209,24 @@ def gate_proj_bwd(c, Ysa, Yswa, Wsa, Wswa, dY):
                                    _p(out.get("dYswa")), _p(out["dWsa"]), _p(out.get("dWswa"))),
            "orc_gate_proj_bwd")
     return out
+
+
+def dual_path_fwd(sa, swa, Q, K, V, perm, Wsa, Wswa):
+    """Alg. 2 as printed: both attention branches, then Eq. 6 gates and the Eq. 5 sum.
+    Returns dict(Y, Ysa, Yswa, LSEsa, LSEswa, Lsa, Lswa) (L* = gate logits)."""
+    Ysa, LSEsa = sa_fwd(sa, Q, K, V, perm)
+    Yswa, LSEswa = sa_fwd(swa, Q, K, V, None)
+    Y, La, Lb = gate_proj_fwd(sa, Ysa, Yswa, Wsa, Wswa, want_logits=True)
+    return dict(Y=Y, Ysa=Ysa, Yswa=Yswa, LSEsa=LSEsa, LSEswa=LSEswa, Lsa=La, Lswa=Lb)
+
+
+def dual_path_bwd(sa, swa, Q, K, V, perm, Wsa, Wswa, dY):
+    """Chain rule through dual_path_fwd: the gate stage hands each branch its own output gradient,
+    each branch is differentiated on its own (Eq. 4 for the permuted one) and dQ, dK, dV are summed.
+    Returns dict(dQ, dK, dV, dWsa, dWswa)."""
+    Ysa, _ = sa_fwd(sa, Q, K, V, perm)
+    Yswa, _ = sa_fwd(swa, Q, K, V, None)
+    g = gate_proj_bwd(sa, Ysa, Yswa, Wsa, Wswa, dY)
+    a = sa_bwd(sa, Q, K, V, perm, g["dYsa"])
+    b = sa_bwd(swa, Q, K, V, None, g["dYswa"])
+    return dict(dQ=a[0] + b[0], dK=a[1] + b[1], dV=a[2] + b[2], dWsa=g["dWsa"], dWswa=g["dWswa"])

@@ -597,3 +597,37 @@ def test_perm_sampler_is_a_uniform_bijection():
     for layer in range(8000):
         cell[np.arange(8), ps.sample_perm(9, layer, 1, 1, 8)[0, 0]] += 1
     assert ((cell - 1000.0) ** 2 / 1000.0).sum() < 100.0   # 49 d.o.f., 99.9 % point 85.4
+
+
+# ------------------------------------------------------------------ Alg. 2 layer: both branches + projected gates
+
+def test_dual_path_layer_against_autograd():
+    """The composed layer (attention branches -> Eq. 6 gates -> Eq. 5 sum) and its chain-rule backward
+    against library autograd on the dense-mask form; the branch that is switched off contributes nothing."""
+    B, Hq, Hkv, n, d, w = 1, 4, 2, 20, 4, 6
+    dm = Hq * d
+    sa = orc.desc(B, Hq, Hkv, n, d, w, orc.WIN_SYM_CIRCULAR, 1)
+    swa = orc.desc(B, Hq, Hkv, n, d, w, orc.WIN_ONE_SIDED, 1)
+    Q, K, V = rnd((B, Hq, n, d), 401), rnd((B, Hkv, n, d), 402), rnd((B, Hkv, n, d), 403)
+    dY = rnd((B, Hq, n, d), 404)
+    Wsa, Wswa = rnd((dm, dm), 405) * 0.7, rnd((dm, dm), 406) * 0.7
+    perm = rand_perm(1, 1, n, 407)
+    fw = orc.dual_path_fwd(sa, swa, Q, K, V, perm, Wsa, Wswa)
+    bw = orc.dual_path_bwd(sa, swa, Q, K, V, perm, Wsa, Wswa, dY)
+    t = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True)
+         for k, v in dict(Q=Q, K=K, V=V, Wsa=Wsa, Wswa=Wswa).items()}
+    tok = lambda Y: Y.permute(0, 2, 1, 3).reshape(B, n, dm)
+    ya = tok(_torch_dense(sa, t["Q"], t["K"], t["V"], perm))
+    yb = tok(_torch_dense(swa, t["Q"], t["K"], t["V"], None))
+    Yt = torch.sigmoid(ya @ t["Wsa"].T) * ya + torch.sigmoid(yb @ t["Wswa"].T) * yb
+    np.testing.assert_allclose(tok(torch.from_numpy(fw["Y"])).numpy(), Yt.detach().numpy(), atol=1e-13)
+    (Yt * tok(torch.from_numpy(dY))).sum().backward()
+    for k, name in (("Q", "dQ"), ("K", "dK"), ("V", "dV"), ("Wsa", "dWsa"), ("Wswa", "dWswa")):
+        np.testing.assert_allclose(bw[name], t[k].grad.numpy(), rtol=1e-11, atol=1e-12, err_msg=name)
+    # gates of exactly one half (zero weights): the layer is the mean of the branches and so is its gradient
+    Z = np.zeros((dm, dm))
+    half = orc.dual_path_bwd(sa, swa, Q, K, V, perm, Z, Z, dY)
+    a = orc.sa_bwd(sa, Q, K, V, perm, 0.5 * dY)
+    b = orc.sa_bwd(swa, Q, K, V, None, 0.5 * dY)
+    for i, name in enumerate(("dQ", "dK", "dV")):
+        np.testing.assert_allclose(half[name], a[i] + b[i], atol=1e-13)
