@@ -131,7 +131,13 @@ def training_ops(sa, synth, dev, reps):
     _, t_gp = time_op(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
     _, t_gpb = time_op(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
                                                    dWsa, dWswa, wsg), reps, 2)
-    del Gsa, Gswa, dYsa, dYswa, wsg
+    # the whole layer of Alg. 2 in one call each way (both branches + gate projections)
+    wsd = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_DUAL_PATH_BWD), device=dev, dtype=torch.uint8)
+    _, t_dpf = time_op(lambda: sa.sa_dual_path_fwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Y, Ysa, Yswa, Gsa, Gswa,
+                                                   Lsa, Lswa), reps, 2)
+    _, t_dpb = time_op(lambda: sa.sa_dual_path_bwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Ysa, Yswa, Gsa, Gswa,
+                                                   Lsa, Lswa, dY, dQ, dK, dV, dWsa, dWswa, wsd), reps, 2)
+    del Gsa, Gswa, dYsa, dYswa, wsg, wsd
     flop_gp = 2 * 2.0 * B * n * dm * dm
     W = band_slots(n, w, 0)
     flop_fb = 14.0 * n * W * d * B * H  # forward 4, backward 10 per (query, in-window slot, d)
@@ -144,7 +150,9 @@ def training_ops(sa, synth, dev, reps):
         "sa_fwdbwd_tokens_per_s": B * n / ((t_fwd + t_bwd) * 1e-3),
         "sa_fwdbwd_band_tflops": flop_fb / ((t_fwd + t_bwd) * 1e-3) / 1e12,
         "gated_fwd_ms": t_gfwd, "gated_bwd_ms": t_gbwd,
-        "gated_fwdbwd_tokens_per_s": B * n / ((t_gfwd + t_gbwd) * 1e-3)}}
+        "gated_fwdbwd_tokens_per_s": B * n / ((t_gfwd + t_gbwd) * 1e-3),
+        "dual_path_layer_fwd_ms": t_dpf, "dual_path_layer_bwd_ms": t_dpb,
+        "dual_path_layer_fwdbwd_tokens_per_s": B * n / ((t_dpf + t_dpb) * 1e-3)}}
 
 
 def long_prefill_ops(sa, synth, dev, reps):

@@ -73,7 +73,8 @@ typedef struct {
 typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BWD = 3,
                SA_OP_CHECK_PERM = 4,
                SA_OP_GATE_PROJ_BWD = 5,        /* sa_gate_proj_bwd, both branches */
-               SA_OP_GATE_PROJ_BWD_SINGLE = 6  /* sa_gate_proj_bwd, single path   */
+               SA_OP_GATE_PROJ_BWD_SINGLE = 6, /* sa_gate_proj_bwd, single path   */
+               SA_OP_DUAL_PATH_BWD = 7         /* sa_dual_path_bwd                */
 } sa_op;
 
 const char* sa_status_string(sa_status s);
@@ -138,6 +139,23 @@ sa_status sa_gate_proj_bwd(const sa_desc* desc, const void* Y_sa, const void* Y_
                            const void* W_swa, const void* G_sa, const void* G_swa, const void* dY,
                            void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
                            void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 2 as printed (the dual-path layer between the Q/K/V and the output projections):
+ *   Y_sa = StochasticAttn(Q,K,V; perm) [sa_fwd with `sa`],  Y_swa = SWA(Q,K,V) [sa_fwd with `swa`, identity],
+ *   g_x = sigmoid(Y_x W_x^T) over the model dimension (Eq. 6),  Y = g_sa * Y_sa + g_swa * Y_swa (Eq. 5).
+ * Y_sa, Y_swa are required buffers [B,Hq,n,d]; G_sa, G_swa, LSE_sa, LSE_swa may be NULL at inference
+ * and are what sa_dual_path_bwd needs.  Same support as sa_gate_proj_fwd.  No workspace. */
+sa_status sa_dual_path_fwd(const sa_desc* sa, const sa_desc* swa, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, const void* W_sa, const void* W_swa, void* Y, void* Y_sa,
+                           void* Y_swa, void* G_sa, void* G_swa, float* LSE_sa, float* LSE_swa, void* stream);
+
+/* Backward of sa_dual_path_fwd: dQ, dK, dV (sums over both branches) and dW_sa, dW_swa from dY.
+ * ws: sa_workspace_bytes(sa, SA_OP_DUAL_PATH_BWD) bytes. */
+sa_status sa_dual_path_bwd(const sa_desc* sa, const sa_desc* swa, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, const void* W_sa, const void* W_swa, const void* Y_sa,
+                           const void* Y_swa, const void* G_sa, const void* G_swa, const float* LSE_sa,
+                           const float* LSE_swa, const void* dY, void* dQ, void* dK, void* dV, void* dW_sa,
+                           void* dW_swa, void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,

@@ -15,11 +15,11 @@ SA_OK, SA_ERR_NULL, SA_ERR_SHAPE, SA_ERR_UNSUPPORTED, SA_ERR_WORKSPACE, SA_ERR_B
 SA_BF16, SA_F32 = 0, 1
 SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
-SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE = 5, 6
+SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD = 5, 6, 7
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
-           "sa_gate_proj_bwd", "sa_sample_perm")
+           "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd")
 
 
 class sa_desc(C.Structure):
@@ -59,6 +59,10 @@ def _load():
     lib.sa_gate_proj_bwd.argtypes = [dp] + [vp] * 12 + [sz, vp]
     lib.sa_sample_perm.restype = C.c_int
     lib.sa_sample_perm.argtypes = [dp, C.c_uint64, C.c_int32, ip, vp]
+    lib.sa_dual_path_fwd.restype = C.c_int
+    lib.sa_dual_path_fwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 10
+    lib.sa_dual_path_bwd.restype = C.c_int
+    lib.sa_dual_path_bwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 14 + [vp, sz, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -131,6 +135,22 @@ def sa_gate_proj_bwd(desc, Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa, dY, dY_sa, dY_
                                  _ptr(G_swa), _ptr(dY), _ptr(dY_sa), _ptr(dY_swa), _ptr(dW_sa), _ptr(dW_swa),
                                  _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
                                  _stream()), "sa_gate_proj_bwd")
+
+
+def sa_dual_path_fwd(sa, swa, Q, K, V, perm, W_sa, W_swa, Y, Y_sa, Y_swa, G_sa=None, G_swa=None,
+                     LSE_sa=None, LSE_swa=None):
+    _check(_lib.sa_dual_path_fwd(C.byref(sa), C.byref(swa), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(W_sa),
+                                 _ptr(W_swa), _ptr(Y), _ptr(Y_sa), _ptr(Y_swa), _ptr(G_sa), _ptr(G_swa),
+                                 _ptr(LSE_sa), _ptr(LSE_swa), _stream()), "sa_dual_path_fwd")
+
+
+def sa_dual_path_bwd(sa, swa, Q, K, V, perm, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_swa, LSE_sa, LSE_swa, dY,
+                     dQ, dK, dV, dW_sa, dW_swa, ws):
+    _check(_lib.sa_dual_path_bwd(C.byref(sa), C.byref(swa), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(W_sa),
+                                 _ptr(W_swa), _ptr(Y_sa), _ptr(Y_swa), _ptr(G_sa), _ptr(G_swa), _ptr(LSE_sa),
+                                 _ptr(LSE_swa), _ptr(dY), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dW_sa),
+                                 _ptr(dW_swa), _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
+                                 _stream()), "sa_dual_path_bwd")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

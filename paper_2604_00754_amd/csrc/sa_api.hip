@@ -93,6 +93,24 @@ BwdWorkspace bwd_workspace(const sa_desc* c, bool gated) {
   return w;
 }
 
+// sa_dual_path_bwd: gate-projection workspace | dY_sa | dY_swa | D_sa | D_swa
+struct DualBwdWorkspace {
+  size_t off_gp, off_dYa, off_dYb, off_Da, off_Db, total;
+};
+
+DualBwdWorkspace dual_bwd_workspace(const sa_desc* c) {
+  DualBwdWorkspace w = {};
+  const size_t rows = (size_t)c->B * c->Hq * c->n;
+  size_t off = 0;
+  w.off_gp = off; off += align256(sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, true));
+  w.off_dYa = off; off += align256(rows * c->d * 2);
+  w.off_dYb = off; off += align256(rows * c->d * 2);
+  w.off_Da = off; off += align256(rows * sizeof(float));
+  w.off_Db = off; off += align256(rows * sizeof(float));
+  w.total = off;
+  return w;
+}
+
 // The bf16 gated forward keeps the first branch's rows in fp32 until the gated sum is rounded.
 size_t gated_fwd_workspace(const sa_desc* c) {
   if (c->dtype != SA_BF16) return 0;
@@ -136,6 +154,7 @@ size_t sa_workspace_bytes(const sa_desc* c, int op) {
     case SA_OP_CHECK_PERM: return align256((size_t)c->perm_B * c->perm_H * c->n * sizeof(int)) + 256;
     case SA_OP_GATE_PROJ_BWD: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, true);
     case SA_OP_GATE_PROJ_BWD_SINGLE: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, false);
+    case SA_OP_DUAL_PATH_BWD: return dual_bwd_workspace(c).total;
     default: return 0;
   }
 }
@@ -220,6 +239,72 @@ sa_status sa_gate_proj_bwd(const sa_desc* c, const void* Y_sa, const void* Y_swa
   if (!ws || ws_bytes < need) return SA_ERR_WORKSPACE;
   return hip_status(sa::launch_gate_proj_bwd_bf16(c->B, c->Hq, c->n, c->d, Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa, dY,
                                                   dY_sa, dY_swa, dW_sa, dW_swa, ws, (hipStream_t)stream));
+}
+
+sa_status sa_dual_path_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, const void* W_sa, const void* W_swa, void* Y, void* Y_sa,
+                           void* Y_swa, void* G_sa, void* G_swa, float* LSE_sa, float* LSE_swa, void* stream) {
+  sa_status s = validate_desc(sa_d);
+  if (s != SA_OK) return s;
+  s = validate_desc(swa_d);
+  if (s != SA_OK) return s;
+  if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
+  if (!Q || !K || !V || !W_sa || !W_swa || !Y || !Y_sa || !Y_swa) return SA_ERR_NULL;
+  if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
+  s = sa_fwd(sa_d, Q, K, V, perm, Y_sa, LSE_sa, nullptr, 0, stream);
+  if (s != SA_OK) return s;
+  s = sa_fwd(swa_d, Q, K, V, nullptr, Y_swa, LSE_swa, nullptr, 0, stream);
+  if (s != SA_OK) return s;
+  return sa_gate_proj_fwd(sa_d, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa, G_swa, stream);
+}
+
+sa_status sa_dual_path_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const void* K, const void* V,
+                           const int32_t* perm, const void* W_sa, const void* W_swa, const void* Y_sa,
+                           const void* Y_swa, const void* G_sa, const void* G_swa, const float* LSE_sa,
+                           const float* LSE_swa, const void* dY, void* dQ, void* dK, void* dV, void* dW_sa,
+                           void* dW_swa, void* ws, size_t ws_bytes, void* stream) {
+  sa_status s = validate_desc(sa_d);
+  if (s != SA_OK) return s;
+  s = validate_desc(swa_d);
+  if (s != SA_OK) return s;
+  if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
+  if (!Q || !K || !V || !W_sa || !W_swa || !Y_sa || !Y_swa || !G_sa || !G_swa || !LSE_sa || !LSE_swa || !dY ||
+      !dQ || !dK || !dV || !dW_sa || !dW_swa)
+    return SA_ERR_NULL;
+  if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
+  const DualBwdWorkspace w = dual_bwd_workspace(sa_d);
+  if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = reinterpret_cast<char*>(ws);
+  void* dYa = base + w.off_dYa;
+  void* dYb = base + w.off_dYb;
+  // Eq. 5 / Eq. 6 backwards: gradients of the two branch outputs and of the gate weights
+  hipError_t e = sa::launch_gate_proj_bwd_bf16(sa_d->B, sa_d->Hq, sa_d->n, sa_d->d, Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa,
+                                               dY, dYa, dYb, dW_sa, dW_swa, base + w.off_gp, st);
+  if (e != hipSuccess) return hip_status(e);
+  // each attention branch on its own gradient; the second adds to the first
+  const void* dO[2] = {dYb, dYa};
+  const void* Yx[2] = {Y_swa, Y_sa};
+  const float* lse[2] = {LSE_swa, LSE_sa};
+  float* D[2] = {reinterpret_cast<float*>(base + w.off_Db), reinterpret_cast<float*>(base + w.off_Da)};
+  const sa_desc* dsc[2] = {swa_d, sa_d};
+  for (int x = 0; x < 2; ++x) {
+    sa::Prep pr = {};
+    pr.rows = sa_d->B * sa_d->Hq * sa_d->n;
+    pr.d = sa_d->d;
+    pr.bf16 = 1;
+    pr.dY = dO[x];
+    pr.Y_a = Yx[x];
+    pr.D_a = D[x];
+    e = sa::launch_bwd_prepare(pr, st);
+    if (e != hipSuccess) return hip_status(e);
+    Pass p = make_pass(dsc[x], Q, K, V, x == 0 ? nullptr : perm);
+    p.dO = dO[x]; p.lse_in = lse[x]; p.Dsum = D[x];
+    p.dQ = dQ; p.dK = dK; p.dV = dV; p.accumulate = x;
+    e = run_bwd(dsc[x], p, st);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  return SA_OK;
 }
 
 sa_status swa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, void* Y, float* LSE,
