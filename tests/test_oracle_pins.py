@@ -631,3 +631,64 @@ def test_dual_path_layer_against_autograd():
     b = orc.sa_bwd(swa, Q, K, V, None, 0.5 * dY)
     for i, name in enumerate(("dQ", "dK", "dV")):
         np.testing.assert_allclose(half[name], a[i] + b[i], atol=1e-13)
+
+
+# ------------------------------------------------------------------ RoPE on original positions (oracle side)
+
+def test_rope_closed_forms_and_complex_form():
+    from oracle import rope as R
+    # d = 2: theta_0 = 1, so position m turns (1, 0) into (cos m, sin m) and (0, 1) into (-sin m, cos m)
+    X = np.tile(np.array([[1.0, 0.0]]), (5, 1))
+    m = np.arange(5.0)
+    np.testing.assert_allclose(R.rope(X), np.stack([np.cos(m), np.sin(m)], -1), atol=1e-15)
+    np.testing.assert_allclose(R.rope(X[:, ::-1].copy()), np.stack([-np.sin(m), np.cos(m)], -1), atol=1e-15)
+    # d = 4, base 10000: theta = (1, 1/100); position 3 of the second pair turns by 0.03 rad
+    x = np.zeros((4, 4)); x[:, 1] = 1.0       # split halves: pair 1 = (x[1], x[3])
+    y = R.rope(x)
+    np.testing.assert_allclose(y[3], [0.0, np.cos(0.03), 0.0, np.sin(0.03)], atol=1e-15)
+    xi = np.zeros((4, 4)); xi[:, 2] = 1.0      # adjacent pairs: pair 1 = (x[2], x[3])
+    np.testing.assert_allclose(R.rope(xi, interleaved=True)[3], [0.0, 0.0, np.cos(0.03), np.sin(0.03)], atol=1e-15)
+    # pos0 shifts the positions; position 0 is the identity
+    z = rnd((2, 3, 7, 8), 501)
+    np.testing.assert_allclose(R.rope(z, pos0=5)[..., :2, :], R.rope(np.concatenate([np.zeros((2, 3, 5, 8)), z], -2))[..., 5:7, :], atol=1e-14)
+    np.testing.assert_array_equal(R.rope(z)[..., 0, :], z[..., 0, :])
+    # complex form (RoFormer Eq. 12 / 13): (x[2i] + j x[2i+1]) * exp(j m theta_i)
+    n, d, base = 7, 8, 500.0
+    zc = z[..., 0::2] + 1j * z[..., 1::2]
+    rot = np.exp(1j * np.arange(n)[:, None] * base ** (-2.0 * np.arange(d // 2) / d)[None, :])
+    yc = zc * rot
+    got = R.rope(z, base=base, interleaved=True)
+    np.testing.assert_allclose(got[..., 0::2], yc.real, atol=1e-14)
+    np.testing.assert_allclose(got[..., 1::2], yc.imag, atol=1e-14)
+    # the two layouts differ only by a fixed reordering of the features
+    order = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])   # split-halves slot -> adjacent-pair slot
+    np.testing.assert_allclose(R.rope(z[..., order], base=base), got[..., order], atol=1e-14)
+    assert np.abs(R.rope(z, base=base) - got).max() > 1e-2
+
+
+def test_rope_is_a_rotation_with_relative_position_scores_and_its_inverse_is_the_gradient():
+    from oracle import rope as R
+    q, k = rnd((3, 40, 16), 511), rnd((3, 40, 16), 512)
+    for il in (False, True):
+        rq, rk = R.rope(q, interleaved=il, pos0=11), R.rope(k, interleaved=il, pos0=11)
+        # norms of every pair are kept, hence of every row
+        np.testing.assert_allclose((rq ** 2).sum(-1), (q ** 2).sum(-1), rtol=1e-13)
+        # <R_m q, R_n k> depends on m - n only (RoFormer Eq. 16): shift both positions by 9
+        s1 = np.einsum("hmd,hnd->hmn", rq, rk)
+        s2 = np.einsum("hmd,hnd->hmn", R.rope(q, interleaved=il, pos0=20), R.rope(k, interleaved=il, pos0=20))
+        np.testing.assert_allclose(s1, s2, atol=1e-11)
+        # and is not position-free: it differs from the unrotated scores
+        assert np.abs(s1 - np.einsum("hmd,hnd->hmn", q, k)).max() > 0.1
+        # inverse undoes the rotation
+        np.testing.assert_allclose(R.rope(rq, interleaved=il, pos0=11, inverse=True), q, atol=1e-13)
+        # backward = inverse rotation of the upstream gradient: autograd through an independent torch form
+        g = rnd(q.shape, 513)
+        t = torch.tensor(q, requires_grad=True)
+        ang = torch.tensor(R.angles(40, 16, pos0=11))
+        c, s = torch.cos(ang), torch.sin(ang)
+        a, b = (t[..., 0::2], t[..., 1::2]) if il else (t[..., :8], t[..., 8:])
+        y1, y2 = a * c - b * s, a * s + b * c
+        yt = torch.stack([y1, y2], -1).flatten(-2) if il else torch.cat([y1, y2], -1)
+        np.testing.assert_allclose(yt.detach().numpy(), rq, atol=1e-14)
+        (yt * torch.tensor(g)).sum().backward()
+        np.testing.assert_allclose(R.rope(g, interleaved=il, pos0=11, inverse=True), t.grad.numpy(), atol=1e-13)
