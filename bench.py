@@ -336,7 +336,15 @@ def main():
         sampled8k = torch.empty((1, 1, 8192), device=dev, dtype=torch.int32)
         _, sp8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k), 10, 2)
         other.update({"sample_perm_n32768_ms": sp_ms, "sample_perm_n8192_ms": sp8_ms})
-        del Y2
+        # RoPE on original positions for Q and K of the headline shape (out of place; table built once)
+        table = torch.empty((wl.n, wl.d // 2, 2), device=dev, dtype=torch.float32)
+        sa.sa_rope_table(wl.n, wl.d, 1e6, 0, table)
+        Kr = torch.empty_like(K)
+        _, rp_ms = time_op(lambda: sa.sa_rope(desc, Q, K, table, Y2, Kr), max(10, args.steps // 4), 5)
+        rp_bytes = 2 * (Q.numel() + K.numel()) * 2
+        other.update({"rope_qk_ms": rp_ms, "rope_qk_GBps": rp_bytes / (rp_ms * 1e-3) / 1e9,
+                      "rope_qk_frac_hbm": rp_bytes / (rp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        del Y2, Kr, table
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
         other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))
 

@@ -140,6 +140,22 @@ sa_status sa_gate_proj_bwd(const sa_desc* desc, const void* Y_sa, const void* Y_
                            void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* App. A ("Attention" item; training paragraph) and Sec. 4.2: RoPE is applied to Q and K with each token's
+ * ORIGINAL position, before any shuffling; RoFormer Sec. 3.2.2 defines the rotation: pair i of the row at
+ * position m turns by m * base^(-2i/d).
+ * sa_rope_table fills table [n][d/2][2] (device, fp32: cos then sin of (pos0 + m) * base^(-2i/d), evaluated in
+ * fp64); it depends on (n, d, base, pos0) only, so a caller builds it once and keeps it.  d = 64 or 128,
+ * base > 1, pos0 >= 0. */
+sa_status sa_rope_table(int32_t n, int32_t d, double base, int32_t pos0, float* table, void* stream);
+
+/* Rotates Q [B,Hq,n,d] and K [B,Hkv,n,d] (desc->dtype; either may be NULL and is then skipped) into Q_out,
+ * K_out (same layout; may alias the inputs).  interleaved = 0: pair i = (x[i], x[i+d/2]) (split halves, the
+ * default reading); 1: pair i = (x[2i], x[2i+1]) (as RoFormer prints it).  inverse = 1 turns by the negative
+ * angle: applied to the gradients of the rotated Q, K it is the backward of this call.  `table` as written by
+ * sa_rope_table for the same n and d.  The result feeds sa_fwd / sa_bwd unchanged. */
+sa_status sa_rope(const sa_desc* desc, const void* Q, const void* K, const float* table, int32_t interleaved,
+                  int32_t inverse, void* Q_out, void* K_out, void* stream);
+
 /* Alg. 2 as printed (the dual-path layer between the Q/K/V and the output projections):
  *   Y_sa = StochasticAttn(Q,K,V; perm) [sa_fwd with `sa`],  Y_swa = SWA(Q,K,V) [sa_fwd with `swa`, identity],
  *   g_x = sigmoid(Y_x W_x^T) over the model dimension (Eq. 6),  Y = g_sa * Y_sa + g_swa * Y_swa (Eq. 5).

@@ -19,7 +19,8 @@ SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD = 5, 6, 7
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
-           "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd")
+           "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
+           "sa_rope_table", "sa_rope")
 
 
 class sa_desc(C.Structure):
@@ -63,6 +64,10 @@ def _load():
     lib.sa_dual_path_fwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 10
     lib.sa_dual_path_bwd.restype = C.c_int
     lib.sa_dual_path_bwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 14 + [vp, sz, vp]
+    lib.sa_rope_table.restype = C.c_int
+    lib.sa_rope_table.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_int32, vp, vp]
+    lib.sa_rope.restype = C.c_int
+    lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -151,6 +156,15 @@ def sa_dual_path_bwd(sa, swa, Q, K, V, perm, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_s
                                  _ptr(LSE_swa), _ptr(dY), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dW_sa),
                                  _ptr(dW_swa), _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
                                  _stream()), "sa_dual_path_bwd")
+
+
+def sa_rope_table(n, d, base, pos0, table):
+    _check(_lib.sa_rope_table(n, d, float(base), pos0, _ptr(table), _stream()), "sa_rope_table")
+
+
+def sa_rope(desc, Q, K, table, Q_out, K_out, interleaved=0, inverse=0):
+    _check(_lib.sa_rope(C.byref(desc), _ptr(Q), _ptr(K), _ptr(table), interleaved, inverse, _ptr(Q_out),
+                        _ptr(K_out), _stream()), "sa_rope")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

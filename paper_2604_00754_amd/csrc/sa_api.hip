@@ -199,6 +199,27 @@ sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t
   return hip_status(sa::launch_sample_perm(perm, c->perm_B * c->perm_H, c->n, seed, layer, (hipStream_t)stream));
 }
 
+sa_status sa_rope_table(int32_t n, int32_t d, double base, int32_t pos0, float* table, void* stream) {
+  if (!table) return SA_ERR_NULL;
+  if (n < 1 || pos0 < 0 || (long long)n + pos0 > 0x7fffffffLL || !(base > 1.0) || isinf(base)) return SA_ERR_SHAPE;
+  if (!(d == 64 || d == 128)) return SA_ERR_UNSUPPORTED;
+  return hip_status(sa::launch_rope_table(table, n, d, base, pos0, (hipStream_t)stream));
+}
+
+sa_status sa_rope(const sa_desc* c, const void* Q, const void* K, const float* table, int32_t interleaved,
+                  int32_t inverse, void* Q_out, void* K_out, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!table || (!Q && !K) || (Q && !Q_out) || (K && !K_out)) return SA_ERR_NULL;
+  if (!(interleaved == 0 || interleaved == 1) || !(inverse == 0 || inverse == 1)) return SA_ERR_SHAPE;
+  const int bf16 = c->dtype == SA_BF16;
+  hipError_t e = hipSuccess;
+  if (Q) e = sa::launch_rope_apply(Q, Q_out, table, c->B * c->Hq, c->n, c->d, bf16, interleaved, inverse, (hipStream_t)stream);
+  if (e == hipSuccess && K)
+    e = sa::launch_rope_apply(K, K_out, table, c->B * c->Hkv, c->n, c->d, bf16, interleaved, inverse, (hipStream_t)stream);
+  return hip_status(e);
+}
+
 sa_status sa_permuted_copy(const sa_desc* c, const void* Q, const void* K, const void* V,
                            const int32_t* perm, void* Y, void* stream) {
   sa_status s = validate_desc(c);

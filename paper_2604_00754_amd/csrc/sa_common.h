@@ -72,6 +72,11 @@ hipError_t launch_gate_proj_bwd_bf16(int B, int Hq, int n, int d, const void* Y_
                                      const void* dY, void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
                                      void* ws, hipStream_t st);
 
+// sa_rope.hip: (cos, sin) table [n][d/2][2] and the rotation of X [heads][n][d] (in place allowed)
+hipError_t launch_rope_table(float* table, int n, int d, double base, int pos0, hipStream_t st);
+hipError_t launch_rope_apply(const void* X, void* Xout, const float* table, int heads, int n, int d, int bf16,
+                             int interleaved, int inverse, hipStream_t st);
+
 // helpers in sa_misc.hip
 hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag,
                              hipStream_t st);

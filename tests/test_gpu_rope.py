@@ -1,0 +1,123 @@
+"""GPU parity of sa_rope_table / sa_rope (RoPE on original positions, App. A / Sec. 4.2; RoFormer Sec. 3.2.2)
+against the fp64 numpy oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_table(n, d, base, pos0):
+    from paper_2604_00754_amd import binding as sa
+    t = torch.full((n, d // 2, 2), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_rope_table(n, d, base, pos0, t)
+    torch.cuda.synchronize()
+    return t
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("base,pos0", [(1e4, 0), (1e6, 0), (1e4, 131072 - 333), (1e6, 2_000_000)])
+def test_table_matches_fp64_angles(d, base, pos0):
+    from oracle import rope as R
+    n = 333
+    print(f"case rope_table n{n} d{d} base{base} pos0 {pos0}", flush=True)
+    t = gpu_table(n, d, base, pos0).cpu().numpy().astype(np.float64)
+    ang = R.angles(n, d, base, pos0)
+    # fp32 rounding of a value in [-1, 1] (6e-8) plus the fp64 angle error (|angle| * 2^-52 * few)
+    assert np.abs(t[..., 0] - np.cos(ang)).max() <= 2e-7
+    assert np.abs(t[..., 1] - np.sin(ang)).max() <= 2e-7
+
+
+def run_apply(B, Hq, Hkv, n, d, dtype, interleaved, base=1e4, pos0=0, seed=0, in_place=False):
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    print(f"case rope B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} {dtype} interleaved={interleaved} base={base} pos0={pos0} "
+          f"in_place={in_place}", flush=True)
+    wl, x = U.make_case(B, Hq, Hkv, n, d, 4, dtype, seed=seed, identity=True)
+    Q, K = U.to_dev(x["Q"], dtype), U.to_dev(x["K"], dtype)
+    q64, k64 = U.to_np64(Q), U.to_np64(K)     # what the kernel reads (bf16-rounded for bf16)
+    table = gpu_table(n, d, base, pos0)
+    desc = sa.make_desc(B, Hq, Hkv, n, d, 4, dtype=sa.SA_BF16 if dtype == "bf16" else sa.SA_F32)
+    Qo = Q if in_place else torch.full_like(Q, float("nan"))
+    Ko = K if in_place else torch.full_like(K, float("nan"))
+    sa.sa_rope(desc, Q, K, table, Qo, Ko, interleaved=interleaved)
+    torch.cuda.synchronize()
+    kw = dict(base=base, pos0=pos0, interleaved=bool(interleaved))
+    rq, rk = R.rope(q64, **kw), R.rope(k64, **kw)
+    U.assert_close(U.to_np64(Qo), rq, dtype, "rope(Q)")
+    U.assert_close(U.to_np64(Ko), rk, dtype, "rope(K)")
+    # inverse: the backward of the rotation, applied to a gradient
+    g = U.to_dev(np.random.default_rng(seed + 9).standard_normal(x["Q"].shape).astype(np.float32), dtype)
+    go = torch.full_like(g, float("nan"))
+    sa.sa_rope(desc, g, None, table, go, None, interleaved=interleaved, inverse=1)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(go), R.rope(U.to_np64(g), inverse=True, **kw), dtype, "rope^T(dQ)")
+    return Qo, Ko
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("interleaved", [0, 1])
+def test_rope_apply(dtype, d, interleaved):
+    run_apply(2, 4, 2, 301, d, dtype, interleaved, seed=d + interleaved)   # ragged last block, GQA
+
+
+def test_rope_in_place_many_heads_and_late_positions():
+    run_apply(1, 9, 3, 130, 64, "bf16", 0, in_place=True, seed=3)          # head count not a multiple of 4
+    run_apply(1, 2, 1, 200, 128, "bf16", 0, base=1e6, pos0=131072 - 200, seed=4)
+    run_apply(1, 2, 1, 200, 128, "f32", 1, base=1e6, pos0=131072 - 200, seed=5)
+    run_apply(1, 1, 1, 1, 64, "f32", 0, seed=6)                            # a single row at position 0: identity
+
+
+def test_rope_then_attention_matches_the_oracle_composition():
+    """fp32 end to end: rotate Q and K on original positions, then SA forward and backward, then the inverse
+    rotation of dQ and dK; against rope -> attention -> rope^T of the oracle."""
+    from oracle import binding as orc
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    B, Hq, Hkv, n, d, w = 1, 4, 2, 260, 64, 32
+    print(f"case rope+sa B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} f32", flush=True)
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, "f32", seed=21, grads=True)
+    c = U.orc_desc(wl, 0, 1)
+    rq, rk = R.rope(x["Q"]), R.rope(x["K"])
+    Yr, _ = orc.sa_fwd(c, rq, rk, x["V"], x["perm"])
+    dq, dk, dv = orc.sa_bwd(c, rq, rk, x["V"], x["perm"], x["dY"])
+    dq, dk = R.rope(dq, inverse=True), R.rope(dk, inverse=True)
+    Q, K, V, dY = (U.to_dev(x[k], "f32") for k in ("Q", "K", "V", "dY"))
+    perm = torch.from_numpy(x["perm"]).to(U.DEV)
+    desc = U.sa_desc(wl, 0, 1)
+    table = gpu_table(n, d, 1e4, 0)
+    Qr, Kr = torch.empty_like(Q), torch.empty_like(K)
+    sa.sa_rope(desc, Q, K, table, Qr, Kr)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.empty((B, Hq, n), device=U.DEV)
+    sa.sa_fwd(desc, Qr, Kr, V, perm, Y, L)
+    dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(desc, None, Qr, Kr, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    sa.sa_rope(desc, dQ, dK, table, dQ, dK, inverse=1)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(Y), Yr, "f32", "Y")
+    for name, got, ref in (("dQ", dQ, dq), ("dK", dK, dk), ("dV", dV, dv)):
+        U.assert_close(U.to_np64(got), ref, "f32", name, scale_abs=max(1.0, float(np.abs(ref).max())))
+
+
+def test_rope_rejects_bad_arguments():
+    from paper_2604_00754_amd import binding as sa
+    t = torch.zeros((8, 32, 2), device=U.DEV)
+    x = torch.zeros((1, 1, 8, 64), device=U.DEV, dtype=torch.bfloat16)
+    desc = sa.make_desc(1, 1, 1, 8, 64, 4)
+    for args, status in (((8, 96, 1e4, 0, t), sa.SA_ERR_UNSUPPORTED), ((8, 64, 1.0, 0, t), sa.SA_ERR_SHAPE),
+                         ((0, 64, 1e4, 0, t), sa.SA_ERR_SHAPE), ((8, 64, 1e4, -1, t), sa.SA_ERR_SHAPE),
+                         ((8, 64, 1e4, 0, None), sa.SA_ERR_NULL)):
+        with pytest.raises(sa.SaError) as e:
+            sa.sa_rope_table(*args)
+        assert e.value.status == status
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_rope(desc, x, None, t, None, None)      # Q without an output
+    assert e.value.status == sa.SA_ERR_NULL
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_rope(desc, x, None, t, x, None, interleaved=2)
+    assert e.value.status == sa.SA_ERR_SHAPE
