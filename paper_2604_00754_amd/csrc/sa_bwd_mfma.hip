@@ -19,52 +19,93 @@ namespace sa {
 namespace {
 
 constexpr int BM = 128;  // stationary slots per workgroup
-constexpr int BN = 64;   // streamed slots per tile
 constexpr int NT = 256;
 
-template <int D>
+// How the causal conjunct (original position of the key <= that of the query) is applied:
+//   CAUSAL_I32 -- compare 32-bit original positions on the fp32 scores (any n),
+//   CAUSAL_I16 -- n <= 65535: biased 16-bit positions, kept in LDS in accumulator order, turn into an
+//                 AND mask on the bf16 pairs that feed the next product (three 2-wide instructions
+//                 per pair instead of two compares and two selects).
+enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+template <int D, int BN_>
 struct Cfg {
-  static constexpr int STR = D + 8;     // bf16 per LDS row (+16 B pad)
-  static constexpr int VPR = D / 8;     // 16-byte vectors per row
+  static constexpr int BN = BN_;         // streamed slots per tile
+  static constexpr int STR = D + 8;      // bf16 per LDS row (+16 B pad)
+  static constexpr int VPR = D / 8;      // 16-byte vectors per row
   static constexpr int RPP = NT / VPR;
   static constexpr int NV = BN / RPP;
-  static constexpr int WRPP = 64 / VPR;
+  static constexpr int WRPP = 64 / VPR;  // rows one wave moves per pass
+  static constexpr int SP = 32 / WRPP;   // passes for a wave's 32 stationary rows
   static constexpr int TILE_BYTES = BN * STR * 2;
-  static constexpr int LDS_BYTES = 2 * TILE_BYTES + 3 * BN * 4;
-  static_assert(4 * 32 * STR * 2 <= 2 * TILE_BYTES, "per-wave staging must fit in the two tiles");
+  static constexpr int STAGE_BYTES = 4 * 32 * STR * 2;  // 32 stationary rows of each of the 4 waves
+  static constexpr int AREA_BYTES = 2 * TILE_BYTES > 2 * STAGE_BYTES ? 2 * TILE_BYTES : 2 * STAGE_BYTES;
+  static constexpr int LDS_BYTES = AREA_BYTES + 3 * BN * 4;
+  static_assert(BN <= NT && BN % 32 == 0 && NV >= 1, "one thread per streamed slot for the per-slot values");
 };
 
-// Stage 32 rows (slots s0 .. s0+31, clamped to n-1) of a [n, D] head through this wave's LDS area
-// and return them as MFMA B operands: lane (g2, c32) gets row c32, elements 16kk + 8*g2 .. +7.
-template <int D>
-__device__ __forceinline__ void load_stationary(const bf16_t* __restrict__ head, const int32_t* __restrict__ perm,
-                                                int s0, int n, bf16_t* stage, int lane, bf16x8* frag) {
-  using C = Cfg<D>;
-  const int chunk16 = lane % C::VPR;
+// LDS exchange inside one wave (a wave's LDS instructions execute in order): only the compiler has to
+// be kept from moving the reads above the writes.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Accumulator i = 4*mq + x of lane group g2 holds tile row 32*kb + 8*mq + 4*g2 + x.  Position of tile
+// row r in "accumulator order": the 16 rows of one (kb, g2) are contiguous, in the order of i.
+__device__ __forceinline__ int acc_order_pos(int r) {
+  return (r & ~31) | (((r >> 2) & 1) << 4) | (((r >> 3) & 3) << 2) | (r & 3);
+}
+
+// The 32 stationary rows of a wave (slots s0 .. s0+31, clamped to n-1) reach the MFMA B-operand layout
+// through a wave-private LDS area, in steps, so that a kernel can put every index load, then every row
+// load of its prologue in flight before it waits for any of them:
+//   stationary_src  -- original positions of the rows this lane moves,
+//   stationary_rows -- the lane's 16-byte pieces of those rows,
+//   stationary_put / stationary_get -- through LDS: lane (g2, c32) gets row c32, elements
+//   16kk + 8*g2 .. +7.
+template <class C>
+__device__ __forceinline__ void stationary_src(const int32_t* __restrict__ perm, int s0, int n, int lane, int* src) {
 #pragma unroll
-  for (int pass = 0; pass < 32 / C::WRPP; ++pass) {
-    const int row = pass * C::WRPP + lane / C::VPR;
-    const int src = slot_to_orig(perm, min(s0 + row, n - 1));
-    const u32x4 v = *reinterpret_cast<const u32x4*>(head + (size_t)src * D + chunk16 * 8);
-    *reinterpret_cast<u32x4*>(stage + row * C::STR + chunk16 * 8) = v;
-  }
-  __syncthreads();
+  for (int pass = 0; pass < C::SP; ++pass)
+    src[pass] = slot_to_orig(perm, min(s0 + pass * C::WRPP + lane / C::VPR, n - 1));
+}
+
+template <class C, int D>
+__device__ __forceinline__ void stationary_rows(const bf16_t* __restrict__ head, const int* src, int lane, u32x4* rows) {
+#pragma unroll
+  for (int pass = 0; pass < C::SP; ++pass)
+    rows[pass] = *reinterpret_cast<const u32x4*>(head + (size_t)src[pass] * D + (lane % C::VPR) * 8);
+}
+
+template <class C>
+__device__ __forceinline__ void stationary_put(bf16_t* stage, int lane, const u32x4* rows) {
+#pragma unroll
+  for (int pass = 0; pass < C::SP; ++pass)
+    *reinterpret_cast<u32x4*>(stage + (pass * C::WRPP + lane / C::VPR) * C::STR + (lane % C::VPR) * 8) = rows[pass];
+}
+
+template <class C, int D>
+__device__ __forceinline__ void stationary_get(const bf16_t* stage, int lane, bf16x8* frag) {
   const int g2 = lane >> 5, c32 = lane & 31;
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk)
     frag[kk] = *reinterpret_cast<const bf16x8*>(stage + c32 * C::STR + 16 * kk + 8 * g2);
-  __syncthreads();
 }
 
 // Write a wave's transposed accumulators (lane = row c32 of the output, 4 consecutive values along
-// d per accumulator quad) as 32 bf16 rows to their original positions.  `accumulate` first adds what
-// the rows already hold, in fp32, so the sum is rounded once.
-template <int D>
-__device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage, bf16_t* out_head,
-                                           const int32_t* perm, int s0, int n, int lane, int accumulate) {
-  using C = Cfg<D>;
+// d per accumulator quad) as 32 bf16 rows to their original positions: src[pass] for the rows this
+// lane moves (as stationary_src gave them), orig_mine for the lane's own row c32.  `accumulate`
+// first adds what the rows already hold, in fp32, so the sum is rounded once.  The staging area is
+// private to the wave.
+template <class C, int D>
+__device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage, bf16_t* out_head, const int* src,
+                                           int orig_mine, int s0, int n, int lane, int accumulate) {
   const int g2 = lane >> 5, c32 = lane & 31;
-  const bf16_t* mine = out_head + (size_t)slot_to_orig(perm, min(s0 + c32, n - 1)) * D;
+  const bf16_t* mine = out_head + (size_t)orig_mine * D;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -81,27 +122,29 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
       w[1] = pack_bf16(v2, v3);
       *reinterpret_cast<u32x2*>(stage + c32 * C::STR + 32 * db + 8 * mq + 4 * g2) = w;
     }
-  __syncthreads();
+  wave_lds_sync();
   const int chunk16 = lane % C::VPR;
 #pragma unroll
-  for (int pass = 0; pass < 32 / C::WRPP; ++pass) {
+  for (int pass = 0; pass < C::SP; ++pass) {
     const int row = pass * C::WRPP + lane / C::VPR;
     if (s0 + row < n) {
-      const size_t eoff = (size_t)slot_to_orig(perm, s0 + row) * D + chunk16 * 8;
+      const size_t eoff = (size_t)src[pass] * D + chunk16 * 8;
       *reinterpret_cast<u32x4*>(out_head + eoff) = *reinterpret_cast<const u32x4*>(stage + row * C::STR + chunk16 * 8);
     }
   }
-  __syncthreads();
+  wave_lds_sync();
 }
 
 // ------------------------------------------------------------------------------------------ dQ
-template <int D>
-__global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
-  using C = Cfg<D>;
+template <int D, int CAUSAL>
+__global__ __launch_bounds__(NT, D == 128 ? 1 : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
+  using C = Cfg<D, 64>;
+  constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
   bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + C::TILE_BYTES);
-  int* pk_lds = reinterpret_cast<int*>(smem + 2 * C::TILE_BYTES);
+  int* pk_lds = reinterpret_cast<int*>(smem + C::AREA_BYTES);
+  short* pk16_lds = reinterpret_cast<short*>(smem + C::AREA_BYTES);  // CAUSAL_I16 keeps 16-bit positions instead
 
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
@@ -116,7 +159,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
-  const bool circular = p.win.circular != 0, causal = p.causal != 0;
+  const bool circular = p.win.circular != 0;
   const int32_t* __restrict__ perm =
       p.perm ? p.perm + (size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * n : nullptr;
   const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
@@ -129,9 +172,6 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
   const int q_last = min(p0 + BM - 1, n - 1);
   const int s_w0 = p0 + 32 * wave;
   const int s = s_w0 + c32;
-  const int orig_q = slot_to_orig(perm, min(s, n - 1));
-  const float lse2 = p.lse_in[head_row0 + orig_q] * kLog2e;
-  const float Dq = p.Dsum[head_row0 + orig_q];
 
   int t_lo = p0 - L, t_hi = q_last + R;
   if (!circular) {
@@ -140,12 +180,8 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
   }
   const int ntiles = (t_hi - t_lo + BN) / BN;
 
-  bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::STR;
-  bf16x8 qf[D / 16], gf[D / 16];
-  load_stationary<D>(Qh, perm, s_w0, n, stage, lane, qf);
-  load_stationary<D>(dOh, perm, s_w0, n, stage, lane, gf);
-
   const int ld_row = tid / C::VPR, ld_chunk = tid % C::VPR;
+  const int pk_pos = acc_order_pos(tid & (BN - 1));
   int idx[C::NV];
   int pk_next = 0;
   auto load_idx = [&](int tile) {
@@ -155,7 +191,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
       const int t = min(t0 + v * C::RPP + ld_row, t_hi);
       idx[v] = slot_to_orig(perm, wrap_slot(t, n));
     }
-    if (tid < BN) pk_next = slot_to_orig(perm, wrap_slot(min(t0 + tid, t_hi), n));
+    if (CAUSAL != CAUSAL_NONE && tid < BN) pk_next = slot_to_orig(perm, wrap_slot(min(t0 + tid, t_hi), n));
   };
   u32x4 kreg[C::NV], vreg[C::NV];
   auto load_rows = [&]() {
@@ -165,8 +201,28 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
       vreg[v] = *reinterpret_cast<const u32x4*>(Vh + (size_t)idx[v] * D + ld_chunk * 8);
     }
   };
+
+  // prologue: every index, then every row (stationary Q and dO, first K/V tile), then the staging
+  int st_src[C::SP];
+  stationary_src<C>(perm, s_w0, n, lane, st_src);
+  const int orig_q = slot_to_orig(perm, min(s, n - 1));
   load_idx(0);
-  load_rows();
+  bf16x8 qf[D / 16], gf[D / 16];
+  {
+    u32x4 qrow[C::SP], grow[C::SP];
+    stationary_rows<C, D>(Qh, st_src, lane, qrow);
+    stationary_rows<C, D>(dOh, st_src, lane, grow);
+    load_rows();
+    bf16_t* stage_q = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::STR;
+    bf16_t* stage_g = reinterpret_cast<bf16_t*>(smem + C::STAGE_BYTES) + wave * 32 * C::STR;
+    stationary_put<C>(stage_q, lane, qrow);
+    stationary_put<C>(stage_g, lane, grow);
+    wave_lds_sync();
+    stationary_get<C, D>(stage_q, lane, qf);
+    stationary_get<C, D>(stage_g, lane, gf);
+  }
+  const float lse2 = p.lse_in[head_row0 + orig_q] * kLog2e;
+  const float Dq = p.Dsum[head_row0 + orig_q];
   int pk_cur = pk_next;
   if (ntiles > 1) load_idx(1);
 
@@ -174,6 +230,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
   const int Rl = circular ? R : min(R, max(n - 1 - s, 0));
   const unsigned LRl = (unsigned)(Ll + Rl);
   const float cs = p.scale * kLog2e;
+  const s16x2 oq1 = {(short)(orig_q + 1 - 32768), (short)(orig_q + 1 - 32768)};
 
   f32x16 dqacc[D / 32];
 #pragma unroll
@@ -189,7 +246,8 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
       *reinterpret_cast<u32x4*>(Ks + row * C::STR + ld_chunk * 8) = kreg[v];
       *reinterpret_cast<u32x4*>(Vs + row * C::STR + ld_chunk * 8) = vreg[v];
     }
-    if (tid < BN) pk_lds[tid] = pk_cur;
+    if (CAUSAL == CAUSAL_I32 && tid < BN) pk_lds[tid] = pk_cur;
+    if (CAUSAL == CAUSAL_I16 && tid < BN) pk16_lds[pk_pos] = (short)(pk_cur - 32768);
     __syncthreads();
     if (tile + 1 < ntiles) {
       load_rows();
@@ -198,7 +256,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
     }
     const int t0 = t_lo + tile * BN;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < BN / 32; ++kb) {
       const int tb0 = t0 + 32 * kb;
       const int dmax = tb0 + 31 - s_w0, dmin = tb0 - (s_w0 + 31);
       const bool act = !(dmax < -L || dmin > R) && tb0 <= t_hi;
@@ -214,7 +272,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
         const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vs + (32 * kb + c32) * C::STR + 16 * kk + 8 * g2);
         dpacc = mfma_bf16(va, gf[kk], dpacc);  // dP^T = V dO^T
       }
-      if (causal) {
+      if (CAUSAL == CAUSAL_I32) {
 #pragma unroll
         for (int mq = 0; mq < 4; ++mq) {
           const int4 pk = *reinterpret_cast<const int4*>(pk_lds + 32 * kb + 8 * mq + 4 * g2);
@@ -232,13 +290,33 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
           if (u > LRl) sacc[i] = -INFINITY;
         }
       }
-      float ds[16];
+      bf16x8 dsf0, dsf1;
+      if (CAUSAL == CAUSAL_I16) {
+        // pair e = accumulators 2e, 2e+1 = dword e of the lane group's 16 positions
+        const uint32_t* pk16 = reinterpret_cast<const uint32_t*>(pk16_lds) + 16 * kb + 8 * g2;
+        const u32x4 ia = *reinterpret_cast<const u32x4*>(pk16), ib = *reinterpret_cast<const u32x4*>(pk16 + 4);
+        u32x4 w[2];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[i], cs, -lse2));
-        ds[i] = pe * (dpacc[i] - Dq);
+        for (int e = 0; e < 8; ++e) {
+          const float pe0 = __builtin_amdgcn_exp2f(fmaf(sacc[2 * e], cs, -lse2));
+          const float pe1 = __builtin_amdgcn_exp2f(fmaf(sacc[2 * e + 1], cs, -lse2));
+          const s16x2 pk2 = __builtin_bit_cast(s16x2, e < 4 ? ia[e & 3] : ib[e & 3]);
+          const s16x2 later = __builtin_elementwise_sub_sat(pk2, oq1);  // >= 0 for keys after the query
+          w[e >> 2][e & 3] = pack_bf16(pe0 * (dpacc[2 * e] - Dq), pe1 * (dpacc[2 * e + 1] - Dq)) &
+                             __builtin_bit_cast(uint32_t, later >> (short)15);
+        }
+        dsf0 = __builtin_bit_cast(bf16x8, w[0]);
+        dsf1 = __builtin_bit_cast(bf16x8, w[1]);
+      } else {
+        float ds[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[i], cs, -lse2));
+          ds[i] = pe * (dpacc[i] - Dq);
+        }
+        dsf0 = pack_b_operand(ds);
+        dsf1 = pack_b_operand(ds + 8);
       }
-      const bf16x8 dsf0 = pack_b_operand(ds), dsf1 = pack_b_operand(ds + 8);
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {  // dQ^T += K^T dS^T
         dqacc[db] = mfma_bf16(lds_read_transposed_a(Ks, C::STR, 32 * kb, 32 * db, lane), dsf0, dqacc[db]);
@@ -247,19 +325,23 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dq_mfma_bf16_kernel(
     }
   }
   __syncthreads();
-  store_rows<D>(dqacc, p.scale, stage, reinterpret_cast<bf16_t*>(p.dQ) + head_row0 * D, perm, s_w0, n, lane, p.accumulate);
+  bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::STR;
+  store_rows<C, D>(dqacc, p.scale, stage, reinterpret_cast<bf16_t*>(p.dQ) + head_row0 * D, st_src, orig_q, s_w0, n, lane,
+                   p.accumulate);
 }
 
 // --------------------------------------------------------------------------------------- dK, dV
-template <int D>
+template <int D, int CAUSAL>
 __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel(const Pass p, const int num_kt, const long total_work) {
-  using C = Cfg<D>;
+  using C = Cfg<D, D == 64 ? 128 : 64>;
+  constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
   bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);
   bf16_t* Gs = reinterpret_cast<bf16_t*>(smem + C::TILE_BYTES);
-  int* pq_lds = reinterpret_cast<int*>(smem + 2 * C::TILE_BYTES);
-  float* lse_lds = reinterpret_cast<float*>(smem + 2 * C::TILE_BYTES + BN * 4);
-  float* dd_lds = reinterpret_cast<float*>(smem + 2 * C::TILE_BYTES + 2 * BN * 4);
+  int* pq_lds = reinterpret_cast<int*>(smem + C::AREA_BYTES);
+  short* pq16_lds = reinterpret_cast<short*>(smem + C::AREA_BYTES);  // CAUSAL_I16 keeps 16-bit positions instead
+  float* lse_lds = reinterpret_cast<float*>(smem + C::AREA_BYTES + BN * 4);
+  float* dd_lds = reinterpret_cast<float*>(smem + C::AREA_BYTES + 2 * BN * 4);
 
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
@@ -271,7 +353,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
-  const bool circular = p.win.circular != 0, causal = p.causal != 0;
+  const bool circular = p.win.circular != 0;
   const bf16_t* __restrict__ Kh = reinterpret_cast<const bf16_t*>(p.K) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   const bf16_t* __restrict__ Vh = reinterpret_cast<const bf16_t*>(p.V) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
 
@@ -305,18 +387,16 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
   const int hg_end = p.hq_only >= 0 ? p.hq_only + 1 : p.g;
   bf16x8 kf[D / 16], vf[D / 16];
   int orig_k = 0;
+  int st_src[C::SP];
+  const int pq_pos = acc_order_pos(tid & (BN - 1));
   for (int hg = hg_begin; hg < hg_end; ++hg) {
     const int hq = hk * p.g + hg;
     const int32_t* __restrict__ perm_h =
         p.perm ? p.perm + (size_t)perm_slice_index(p.perm_B, p.perm_H, b, hq) * n : nullptr;
-    if (hg == hg_begin || perm_h != perm) {
-      // (re)load the stationary K and V rows; with one permutation per group this happens once
-      perm = perm_h;
-      __syncthreads();
-      load_stationary<D>(Kh, perm, t_w0, n, stage, lane, kf);
-      load_stationary<D>(Vh, perm, t_w0, n, stage, lane, vf);
-      orig_k = slot_to_orig(perm, min(t, n - 1));
-    }
+    // the stationary K and V rows are (re)loaded when the slot order changes; with one permutation
+    // per group that is once
+    const bool reload = hg == hg_begin || perm_h != perm;
+    perm = perm_h;
     const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
     const bf16_t* __restrict__ Qh = reinterpret_cast<const bf16_t*>(p.Q) + head_row0 * D;
     const bf16_t* __restrict__ dOh = reinterpret_cast<const bf16_t*>(p.dO) + head_row0 * D;
@@ -350,9 +430,30 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
         dd_reg = dd_h[pq_next];
       }
     };
+    // every index first, then every row (stationary K and V, first Q/dO tile), then the staging
+    if (reload) {
+      stationary_src<C>(perm, t_w0, n, lane, st_src);
+      orig_k = slot_to_orig(perm, min(t, n - 1));
+    }
     load_idx(0);
-    load_rows();
+    if (reload) {
+      u32x4 krow[C::SP], vrow[C::SP];
+      stationary_rows<C, D>(Kh, st_src, lane, krow);
+      stationary_rows<C, D>(Vh, st_src, lane, vrow);
+      load_rows();
+      bf16_t* stage_v = reinterpret_cast<bf16_t*>(smem + C::STAGE_BYTES) + wave * 32 * C::STR;
+      if (hg != hg_begin) __syncthreads();  // a slower wave may still read the previous head's last tile
+      stationary_put<C>(stage, lane, krow);
+      stationary_put<C>(stage_v, lane, vrow);
+      wave_lds_sync();
+      stationary_get<C, D>(stage, lane, kf);
+      stationary_get<C, D>(stage_v, lane, vf);
+    } else {
+      load_rows();
+    }
     if (ntiles > 1) load_idx(1);
+    // visible iff the query's original position >= the key's: (orig_k - 1) - pq < 0, on positions biased by 32767
+    const s16x2 okm1 = {(short)(orig_k - 32768), (short)(orig_k - 32768)};
 
     for (int tile = 0; tile < ntiles; ++tile) {
       __syncthreads();
@@ -363,7 +464,8 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
         *reinterpret_cast<u32x4*>(Gs + row * C::STR + ld_chunk * 8) = greg[v];
       }
       if (tid < BN) {
-        pq_lds[tid] = pq_cur;
+        if (CAUSAL == CAUSAL_I32) pq_lds[tid] = pq_cur;
+        if (CAUSAL == CAUSAL_I16) pq16_lds[pq_pos] = (short)(pq_cur - 32767);
         lse_lds[tid] = lse_reg;
         dd_lds[tid] = dd_reg;
       }
@@ -374,7 +476,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
       }
       const int s0 = s_lo + tile * BN;
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 0; qb < BN / 32; ++qb) {
         const int sb0 = s0 + 32 * qb;
         const int dmax = t_w0 + 31 - sb0, dmin = t_w0 - (sb0 + 31);  // range of t - s over the block
         const bool act = !(dmax < -L || dmin > R) && sb0 <= s_hi;
@@ -391,7 +493,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
           dpacc = mfma_bf16(ga, vf[kk], dpacc);  // dP = dO V^T
         }
         // accumulator i is query row 32*qb + 8*(i/4) + 4*g2 + i%4 of the tile, key column = lane
-        if (causal) {
+        if (CAUSAL == CAUSAL_I32) {
 #pragma unroll
           for (int mq = 0; mq < 4; ++mq) {
             const int4 pq = *reinterpret_cast<const int4*>(pq_lds + 32 * qb + 8 * mq + 4 * g2);
@@ -421,8 +523,24 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
             ds[i] = pe[i] * (dpacc[i] - d4[x]);
           }
         }
-        const bf16x8 pf0 = pack_b_operand(pe), pf1 = pack_b_operand(pe + 8);
-        const bf16x8 dsf0 = pack_b_operand(ds), dsf1 = pack_b_operand(ds + 8);
+        bf16x8 pf0, pf1, dsf0, dsf1;
+        if (CAUSAL == CAUSAL_I16) {
+          const uint32_t* pq16 = reinterpret_cast<const uint32_t*>(pq16_lds) + 16 * qb + 8 * g2;
+          const u32x4 ia = *reinterpret_cast<const u32x4*>(pq16), ib = *reinterpret_cast<const u32x4*>(pq16 + 4);
+          u32x4 wp[2], wd[2];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const s16x2 pq2 = __builtin_bit_cast(s16x2, e < 4 ? ia[e & 3] : ib[e & 3]);
+            const uint32_t vis = __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(okm1, pq2) >> (short)15);
+            wp[e >> 2][e & 3] = pack_bf16(pe[2 * e], pe[2 * e + 1]) & vis;
+            wd[e >> 2][e & 3] = pack_bf16(ds[2 * e], ds[2 * e + 1]) & vis;
+          }
+          pf0 = __builtin_bit_cast(bf16x8, wp[0]); pf1 = __builtin_bit_cast(bf16x8, wp[1]);
+          dsf0 = __builtin_bit_cast(bf16x8, wd[0]); dsf1 = __builtin_bit_cast(bf16x8, wd[1]);
+        } else {
+          pf0 = pack_b_operand(pe); pf1 = pack_b_operand(pe + 8);
+          dsf0 = pack_b_operand(ds); dsf1 = pack_b_operand(ds + 8);
+        }
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
           // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over the 32 query rows of the block)
@@ -437,9 +555,11 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
   __syncthreads();
   bf16_t* dKh = reinterpret_cast<bf16_t*>(p.dK) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   bf16_t* dVh = reinterpret_cast<bf16_t*>(p.dV) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
-  store_rows<D>(dkacc, p.scale, stage, dKh, perm, t_w0, n, lane, p.accumulate);
-  store_rows<D>(dvacc, 1.f, stage, dVh, perm, t_w0, n, lane, p.accumulate);
+  store_rows<C, D>(dkacc, p.scale, stage, dKh, st_src, orig_k, t_w0, n, lane, p.accumulate);
+  store_rows<C, D>(dvacc, 1.f, stage, dVh, st_src, orig_k, t_w0, n, lane, p.accumulate);
 }
+
+inline int causal_mode(const Pass& p) { return !p.causal ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32); }
 
 template <int D>
 hipError_t launch_dq_t(const Pass& p, hipStream_t st) {
@@ -447,7 +567,12 @@ hipError_t launch_dq_t(const Pass& p, hipStream_t st) {
   const long total = (long)num_qt * p.Hq * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_qt, total);
+  const dim3 grid((unsigned)blocks), block(NT);
+  switch (causal_mode(p)) {
+    case CAUSAL_NONE: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_NONE>), grid, block, 0, st, p, num_qt, total); break;
+    case CAUSAL_I16: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I16>), grid, block, 0, st, p, num_qt, total); break;
+    default: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I32>), grid, block, 0, st, p, num_qt, total); break;
+  }
   return hipGetLastError();
 }
 
@@ -457,7 +582,12 @@ hipError_t launch_dkv_t(const Pass& p, hipStream_t st) {
   const long total = (long)num_kt * p.Hkv * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((bwd_dkv_mfma_bf16_kernel<D>), dim3((unsigned)blocks), dim3(NT), 0, st, p, num_kt, total);
+  const dim3 grid((unsigned)blocks), block(NT);
+  switch (causal_mode(p)) {
+    case CAUSAL_NONE: hipLaunchKernelGGL((bwd_dkv_mfma_bf16_kernel<D, CAUSAL_NONE>), grid, block, 0, st, p, num_kt, total); break;
+    case CAUSAL_I16: hipLaunchKernelGGL((bwd_dkv_mfma_bf16_kernel<D, CAUSAL_I16>), grid, block, 0, st, p, num_kt, total); break;
+    default: hipLaunchKernelGGL((bwd_dkv_mfma_bf16_kernel<D, CAUSAL_I32>), grid, block, 0, st, p, num_kt, total); break;
+  }
   return hipGetLastError();
 }
 
