@@ -18,6 +18,18 @@
 namespace sa {
 namespace {
 
+#ifndef DKV_WAVES
+#define DKV_WAVES 2
+#endif
+#ifndef DQ128_WAVES
+#define DQ128_WAVES 2
+#endif
+#ifndef DKV128_WAVES
+#define DKV128_WAVES 1
+#endif
+#ifndef DKV_BN
+#define DKV_BN 128
+#endif
 constexpr int BM = 128;  // stationary slots per workgroup
 constexpr int NT = 256;
 
@@ -137,7 +149,7 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
 
 // ------------------------------------------------------------------------------------------ dQ
 template <int D, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 128 ? 1 : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
+__global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
   using C = Cfg<D, 64>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
@@ -332,8 +344,8 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 3) void bwd_dq_mfma_bf16_kernel(
 
 // --------------------------------------------------------------------------------------- dK, dV
 template <int D, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel(const Pass p, const int num_kt, const long total_work) {
-  using C = Cfg<D, D == 64 ? 128 : 64>;
+__global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_dkv_mfma_bf16_kernel(const Pass p, const int num_kt, const long total_work) {
+  using C = Cfg<D, D == 64 ? DKV_BN : 64>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
   bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);
@@ -467,7 +479,7 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
         if (CAUSAL == CAUSAL_I32) pq_lds[tid] = pq_cur;
         if (CAUSAL == CAUSAL_I16) pq16_lds[pq_pos] = (short)(pq_cur - 32767);
         lse_lds[tid] = lse_reg;
-        dd_lds[tid] = dd_reg;
+        dd_lds[tid] = -dd_reg;  // dP starts from -D, so that the product leaves dP - D
       }
       __syncthreads();
       if (tile + 1 < ntiles) {
@@ -484,7 +496,11 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
         if (!act) continue;
         f32x16 sacc, dpacc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+        for (int mq = 0; mq < 4; ++mq) {
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dd_lds + 32 * qb + 8 * mq + 4 * g2);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) { sacc[4 * mq + x] = 0.f; dpacc[4 * mq + x] = d4[x]; }
+        }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
           const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qs + (32 * qb + c32) * C::STR + 16 * kk + 8 * g2);
@@ -515,12 +531,11 @@ __global__ __launch_bounds__(NT, D == 128 ? 1 : 2) void bwd_dkv_mfma_bf16_kernel
 #pragma unroll
         for (int mq = 0; mq < 4; ++mq) {
           const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_lds + 32 * qb + 8 * mq + 4 * g2);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dd_lds + 32 * qb + 8 * mq + 4 * g2);
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
             const int i = 4 * mq + x;
             pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], cs, -l4[x]));
-            ds[i] = pe[i] * (dpacc[i] - d4[x]);
+            ds[i] = pe[i] * dpacc[i];  // dpacc = dP - D
           }
         }
         bf16x8 pf0, pf1, dsf0, dsf1;
