@@ -314,6 +314,13 @@ def main():
         pc_bytes = alg_bytes - wl.B * wl.Hq * wl.n * 4  # no LSE
         other.update({"permuted_copy_ms": pc_ms, "permuted_copy_GBps": pc_bytes / (pc_ms * 1e-3) / 1e9,
                       "permuted_copy_frac_hbm": pc_bytes / (pc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        # a plain device-to-device copy of the same number of bytes (torch's copy kernel): what a read+write
+        # stream with no index tensor reaches on this GPU
+        flat_src = torch.empty(pc_bytes // 2, device=dev, dtype=torch.uint8)
+        flat_dst = torch.empty_like(flat_src)
+        _, cp_ms = time_op(lambda: flat_dst.copy_(flat_src), max(10, args.steps // 4), 5)
+        other.update({"plain_copy_ms": cp_ms, "plain_copy_GBps": pc_bytes / (cp_ms * 1e-3) / 1e9})
+        del flat_src, flat_dst
         # the headline launch with cold caches: a 1 GiB device copy between launches evicts L2 and MALL
         if copy_src is None:
             cs = torch.zeros(256 * 1024 * 1024, device=dev, dtype=torch.float32)
@@ -345,6 +352,16 @@ def main():
         other.update({"rope_qk_ms": rp_ms, "rope_qk_GBps": rp_bytes / (rp_ms * 1e-3) / 1e9,
                       "rope_qk_frac_hbm": rp_bytes / (rp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
         del Y2, Kr, table
+        # backward of the headline shape (not a workload of the paper, which trains at d = 64): dQ, dK, dV from dY
+        dYh = torch.randn(Q.shape, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        dQh, dKh, dVh = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        wsh = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=dev, dtype=torch.uint8)
+        sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
+        _, bw_ms = time_op(lambda: sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, LSE, None, dYh,
+                                             dQh, dKh, dVh, None, None, wsh), max(5, args.steps // 20), 2)
+        other.update({"sa_bwd_headline_shape_ms": bw_ms,
+                      "sa_fwdbwd_headline_shape_band_tflops": 3.5 * band_flop / ((ms_per_step + bw_ms) * 1e-3) / 1e12})
+        del dYh, dQh, dKh, dVh, wsh
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
         other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))
 
