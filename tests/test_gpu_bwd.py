@@ -15,10 +15,17 @@ def grad_close(got, ref, dtype, what):
     U.assert_close(got, ref, dtype, what, scale_abs=max(1.0, float(np.abs(ref).max())))
 
 
-def run_bwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed=0, identity=False):
+def run_bwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed=0, identity=False,
+            k_growth=0.0):
     from oracle import binding as orc
     from paper_2604_00754_amd import binding as sa
     wl, x = U.make_case(B, Hq, Hkv, n, d, w, dtype, perm_B, perm_H, seed, grads=True, identity=identity)
+    if k_growth:  # keys grow with their original position: later (masked) keys outscore the visible ones
+        from paper_2604_00754_amd import synth
+        ramp = (1.0 + k_growth * np.arange(n, dtype=np.float32) / n)[None, None, :, None]
+        x["K"] = (x["K"] * ramp).astype(np.float32)
+        if dtype == "bf16":
+            x["K"] = synth.round_to_bf16(x["K"])
     print(f"case bwd B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} win{window} causal{causal} {dtype} "
           f"perm[{perm_B},{perm_H}] identity={identity}", flush=True)
     oc = U.orc_desc(wl, window, causal)
@@ -116,3 +123,20 @@ def test_gated_bwd_bf16(per_dim, gate_dtype):
 
 def test_gated_bwd_bf16_d128():
     run_gated_bwd(1, 4, 1, 500, 128, 96, "bf16", seed=41)
+
+
+def test_bwd_bf16_later_keys_dominate():
+    """Scores of later (causally masked) keys far above the visible ones: in the 16-bit causal mode
+    exp(score - LSE) of such a pair is many orders of magnitude above one before the packed mask clears
+    it, and must leave no trace in dQ, dK, dV.  (The growth is kept where the visible scores stay benign:
+    a steeper ramp makes the softmax of late rows one-hot and the bf16 gradient itself ill-conditioned,
+    rel-L2 5.0e-3 at a ramp of 10.)"""
+    run_bwd(1, 2, 2, 1500, 64, 256, CIRC, 1, "bf16", seed=70, k_growth=4.0)
+    run_bwd(1, 2, 1, 900, 128, 128, CIRC, 1, "bf16", perm_H=2, seed=71, k_growth=3.0)
+
+
+@pytest.mark.parametrize("n", [65535, 65536])
+def test_bwd_bf16_index_width_boundary(n):
+    """The largest n of the 16-bit causal mode and the first n of the 32-bit mode, both backward kernels."""
+    run_bwd(1, 1, 1, n, 64, 32, CIRC, 1, "bf16", seed=72)
+    run_bwd(1, 2, 1, n, 128, 32, ONE, 1, "bf16", seed=73, identity=True)
