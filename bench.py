@@ -351,6 +351,12 @@ def main():
         rp_bytes = 2 * (Q.numel() + K.numel()) * 2
         other.update({"rope_qk_ms": rp_ms, "rope_qk_GBps": rp_bytes / (rp_ms * 1e-3) / 1e9,
                       "rope_qk_frac_hbm": rp_bytes / (rp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        # the prefill sequence of Sec. 4.2 with the Q rotation fused: rotate K in memory, then sa_fwd_rope
+        def rope_then_attention():
+            sa.sa_rope(desc, None, K, table, None, Kr)
+            sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, LSE)
+        _, rf_ms = time_op(rope_then_attention, max(10, args.steps // 4), 5)
+        other.update({"rope_k_plus_fwd_rope_ms": rf_ms, "rope_qk_plus_fwd_ms": rp_ms + ms_per_step})
         del Y2, Kr, table
         # backward of the headline shape (not a workload of the paper, which trains at d = 64): dQ, dK, dV from dY
         dYh = torch.randn(Q.shape, device=dev, dtype=torch.float32).to(torch.bfloat16)

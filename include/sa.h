@@ -156,6 +156,14 @@ sa_status sa_rope_table(int32_t n, int32_t d, double base, int32_t pos0, float* 
 sa_status sa_rope(const sa_desc* desc, const void* Q, const void* K, const float* table, int32_t interleaved,
                   int32_t inverse, void* Q_out, void* K_out, void* stream);
 
+/* sa_fwd with the rotation of Q fused into its load path (the prefill setting of Sec. 4.2: RoPE on original
+ * positions, then stochastic attention): Q arrives UNROTATED and each query row is rotated on its original
+ * position while it is staged; K arrives ROTATED (sa_rope with Q = NULL; a K row is reused by every query
+ * head of its group and by several workgroups, so it is rotated once, in memory).  rope_table, interleaved: as
+ * for sa_rope.  perm = NULL: identity.  bf16 only (SA_ERR_UNSUPPORTED otherwise).  No workspace. */
+sa_status sa_fwd_rope(const sa_desc* desc, const void* Q, const void* K, const void* V, const int32_t* perm,
+                      const float* rope_table, int32_t interleaved, void* Y, float* LSE, void* stream);
+
 /* Alg. 2 as printed (the dual-path layer between the Q/K/V and the output projections):
  *   Y_sa = StochasticAttn(Q,K,V; perm) [sa_fwd with `sa`],  Y_swa = SWA(Q,K,V) [sa_fwd with `swa`, identity],
  *   g_x = sigmoid(Y_x W_x^T) over the model dimension (Eq. 6),  Y = g_sa * Y_sa + g_swa * Y_swa (Eq. 5).

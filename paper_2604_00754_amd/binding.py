@@ -20,7 +20,7 @@ SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD = 5, 6, 7
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
            "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
-           "sa_rope_table", "sa_rope")
+           "sa_rope_table", "sa_rope", "sa_fwd_rope")
 
 
 class sa_desc(C.Structure):
@@ -66,6 +66,8 @@ def _load():
     lib.sa_dual_path_bwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 14 + [vp, sz, vp]
     lib.sa_rope_table.restype = C.c_int
     lib.sa_rope_table.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_int32, vp, vp]
+    lib.sa_fwd_rope.restype = C.c_int
+    lib.sa_fwd_rope.argtypes = [dp, vp, vp, vp, ip, vp, C.c_int32, vp, vp, vp]
     lib.sa_rope.restype = C.c_int
     lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.swa_fwd.restype = C.c_int
@@ -156,6 +158,11 @@ def sa_dual_path_bwd(sa, swa, Q, K, V, perm, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_s
                                  _ptr(LSE_swa), _ptr(dY), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dW_sa),
                                  _ptr(dW_swa), _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
                                  _stream()), "sa_dual_path_bwd")
+
+
+def sa_fwd_rope(desc, Q, K, V, perm, table, Y, LSE=None, interleaved=0):
+    _check(_lib.sa_fwd_rope(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(table), interleaved,
+                            _ptr(Y), _ptr(LSE), _stream()), "sa_fwd_rope")
 
 
 def sa_rope_table(n, d, base, pos0, table):

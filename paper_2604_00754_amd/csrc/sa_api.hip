@@ -199,6 +199,21 @@ sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t
   return hip_status(sa::launch_sample_perm(perm, c->perm_B * c->perm_H, c->n, seed, layer, (hipStream_t)stream));
 }
 
+sa_status sa_fwd_rope(const sa_desc* c, const void* Q, const void* K, const void* V, const int32_t* perm,
+                      const float* rope_table, int32_t interleaved, void* Y, float* LSE, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Q || !K || !V || !Y || !rope_table) return SA_ERR_NULL;
+  if (!(interleaved == 0 || interleaved == 1)) return SA_ERR_SHAPE;
+  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  Pass p = make_pass(c, Q, K, V, perm);
+  p.Y = Y;
+  p.LSE = LSE;
+  p.rope_table = rope_table;
+  p.rope_interleaved = interleaved;
+  return hip_status(run_fwd(c, p, (hipStream_t)stream));
+}
+
 sa_status sa_rope_table(int32_t n, int32_t d, double base, int32_t pos0, float* table, void* stream) {
   if (!table) return SA_ERR_NULL;
   if (n < 1 || pos0 < 0 || (long long)n + pos0 > 0x7fffffffLL || !(base > 1.0) || isinf(base)) return SA_ERR_SHAPE;

@@ -26,6 +26,10 @@ struct Pass {
   Window win;
   int causal;
   float scale;          // softmax scale (Eq. 1)
+  // bf16 forward only: rotate the Q rows on their original positions while they are staged (RoPE table
+  // [n][d/2][2] of sa_rope_table; nullptr = Q arrives rotated).  K always arrives rotated.
+  const float* rope_table;
+  int rope_interleaved;
   // forward outputs
   void* Y;              // branch output rows, may be nullptr when only the gated sum is wanted
   float* LSE;           // may be nullptr

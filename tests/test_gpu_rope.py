@@ -121,3 +121,57 @@ def test_rope_rejects_bad_arguments():
     with pytest.raises(sa.SaError) as e:
         sa.sa_rope(desc, x, None, t, x, None, interleaved=2)
     assert e.value.status == sa.SA_ERR_SHAPE
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("interleaved", [0, 1])
+def test_forward_with_fused_query_rotation(d, interleaved):
+    """sa_fwd_rope (Q rotated on original positions while it is staged, K rotated in memory by sa_rope)
+    against rope -> attention of the oracle in fp64, and against the unfused GPU path."""
+    from oracle import binding as orc
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    B, Hq, Hkv, n, w = 2, 4, 2, 700, 128
+    for identity, window in ((False, 0), (True, 2)):
+        print(f"case fwd_rope B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} interleaved={interleaved} identity={identity}",
+              flush=True)
+        wl, x = U.make_case(B, Hq, Hkv, n, d, w, "bf16", 1, 1 if identity else Hq, seed=80 + d + interleaved,
+                            identity=identity)
+        Q, K, V = (U.to_dev(x[k], "bf16") for k in "QKV")
+        kw = dict(base=1e4, pos0=0, interleaved=bool(interleaved))
+        # in the bf16 configuration the rotated rows are bf16 values (that is where both GPU paths round):
+        # the oracle rotates in fp64 and rounds to bf16 with the input generator's rounding routine
+        from paper_2604_00754_amd import synth
+        rq = synth.round_to_bf16(R.rope(U.to_np64(Q), **kw).astype(np.float32))
+        rk = synth.round_to_bf16(R.rope(U.to_np64(K), **kw).astype(np.float32))
+        Yr, Lr = orc.sa_fwd(U.orc_desc(wl, window, 1), rq, rk, U.to_np64(V), x["perm"])
+        perm = None if identity else torch.from_numpy(x["perm"]).to(U.DEV)
+        desc = U.sa_desc(wl, window, 1)
+        table = gpu_table(n, d, 1e4, 0)
+        Kr, Qr = torch.empty_like(K), torch.empty_like(Q)
+        sa.sa_rope(desc, None, K, table, None, Kr, interleaved=interleaved)
+        Y = torch.full_like(Q, float("nan"))
+        L = torch.full((B, Hq, n), float("nan"), device=U.DEV)
+        sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, L, interleaved=interleaved)
+        sa.sa_rope(desc, Q, None, table, Qr, None, interleaved=interleaved)
+        Y2 = torch.full_like(Q, float("nan"))
+        sa.sa_fwd(desc, Qr, Kr, V, perm, Y2, None)
+        torch.cuda.synchronize()
+        U.assert_close(U.to_np64(Y), Yr, "bf16", "Y (fused rotation)")
+        assert np.abs(U.to_np64(L) - Lr).max() <= 4e-3
+        # the two GPU paths round the rotated Q to bf16 at the same point; they may differ by how the
+        # compiler contracts a*c - b*s, i.e. by single bf16 steps of single Q elements
+        U.assert_close(U.to_np64(Y), U.to_np64(Y2), "bf16", "fused vs unfused")
+
+
+def test_fwd_rope_rejects_unsupported():
+    from paper_2604_00754_amd import binding as sa
+    t = torch.zeros((8, 32, 2), device=U.DEV)
+    x = torch.zeros((1, 1, 8, 64), device=U.DEV, dtype=torch.float32)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_fwd_rope(sa.make_desc(1, 1, 1, 8, 64, 4, dtype=sa.SA_F32), x, x, x, None, t, torch.empty_like(x))
+    assert e.value.status == sa.SA_ERR_UNSUPPORTED
+    xb = x.to(torch.bfloat16)
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_fwd_rope(sa.make_desc(1, 1, 1, 8, 64, 4), xb, xb, xb, None, None, torch.empty_like(xb))
+    assert e.value.status == sa.SA_ERR_NULL
