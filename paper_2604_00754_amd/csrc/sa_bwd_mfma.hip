@@ -574,7 +574,12 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
   store_rows<C, D>(dvacc, 1.f, stage, dVh, st_src, orig_k, t_w0, n, lane, p.accumulate);
 }
 
-inline int causal_mode(const Pass& p) { return !p.causal ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32); }
+inline int causal_mode(const Pass& p) {
+  // identity order with a one-sided linear window (plain causal SWA): the window already excludes every
+  // later key, the causal test would only repeat it
+  const bool window_is_causal = !p.perm && !p.win.circular && p.win.R == 0;
+  return (!p.causal || window_is_causal) ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
+}
 
 template <int D>
 hipError_t launch_dq_t(const Pass& p, hipStream_t st) {

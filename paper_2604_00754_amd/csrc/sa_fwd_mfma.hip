@@ -508,7 +508,10 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks), block(NT);
-  const int mode = !p.causal ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
+  // identity order with a one-sided linear window (plain causal SWA): the window already excludes every
+  // later key, the causal test would only repeat it
+  const bool window_is_causal = !p.perm && !p.win.circular && p.win.R == 0;
+  const int mode = (!p.causal || window_is_causal) ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
 #define SA_LAUNCH_FWD(PERM_, MODE_) \
   hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_>), grid, block, 0, st, p, num_qt, total)
   if (p.perm) {
