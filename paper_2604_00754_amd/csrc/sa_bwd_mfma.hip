@@ -141,7 +141,8 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
     const int row = pass * C::WRPP + lane / C::VPR;
     if (s0 + row < n) {
       const size_t eoff = (size_t)src[pass] * D + chunk16 * 8;
-      *reinterpret_cast<u32x4*>(out_head + eoff) = *reinterpret_cast<const u32x4*>(stage + row * C::STR + chunk16 * 8);
+      __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + row * C::STR + chunk16 * 8),
+                                  reinterpret_cast<u32x4*>(out_head + eoff));
     }
   }
   wave_lds_sync();

@@ -61,6 +61,14 @@ __device__ __forceinline__ u32x4 load_row_chunk(const bf16_t* head, int row, int
   return *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(head) + off);
 }
 
+// The same for rows that are read once (the query rows): a non-temporal load, so that the streamed rows do
+// not displace the K/V rows that neighbouring workgroups share in L2.
+template <int D>
+__device__ __forceinline__ u32x4 load_row_chunk_once(const bf16_t* head, int row, int chunk) {
+  const uint32_t off = (uint32_t)row * (uint32_t)(D * 2) + (uint32_t)chunk * 16u;
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(head) + off));
+}
+
 // Causal test modes.  CAUSAL_NONE: no test.  CAUSAL_I32: scores of later keys are set to -inf before
 // the softmax (any n).  CAUSAL_I16 (n <= 65535): the probabilities of later keys are cleared after
 // they are packed to bf16 pairs, with packed 16-bit compares on biased original indices.
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   {
     u32x4 v[NP];
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) v[pass] = load_row_chunk<D>(Qh, src[pass], chunk16);
+    for (int pass = 0; pass < NP; ++pass) v[pass] = load_row_chunk_once<D>(Qh, src[pass], chunk16);
     load_rows(0);
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass)
@@ -467,8 +475,8 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       const int row = pass * C::WRPP + lane / C::VPR;
       if (s_w0 + row < n) {
         const size_t eoff = (head_row0 + dst[pass]) * D + chunk16 * 8;
-        *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(dst_tensor) + eoff) =
-            *reinterpret_cast<const u32x4*>(Os + row * C::KSTR + chunk16 * 8);
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Os + row * C::KSTR + chunk16 * 8),
+                                    reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(dst_tensor) + eoff));
       }
     }
   };

@@ -63,10 +63,11 @@ __global__ __launch_bounds__(256) void permuted_copy_bf16_kernel(const Pass p, c
       lead[j] = hq % p.g == 0;
       const size_t qoff = ((size_t)bh * p.n + src[j]) * d + sub * 8;
       const size_t koff = (((size_t)b * p.Hkv + hq / p.g) * p.n + src[j]) * d + sub * 8;
-      q[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.Q) + qoff);
+      // every row is touched once: non-temporal loads and stores
+      q[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.Q) + qoff));
       if (lead[j]) {
-        k[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.K) + koff);
-        v[j] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.V) + koff);
+        k[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.K) + koff));
+        v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.V) + koff));
       }
     }
 #pragma unroll
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void permuted_copy_bf16_kernel(const Pass p, c
                            bf16hi(q[j][e]) + bf16hi(k[j][e]) + bf16hi(v[j][e]));
       }
       const size_t qoff = ((size_t)(r[j] / p.n) * p.n + src[j]) * d + sub * 8;
-      *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.Y) + qoff) = o;
+      __builtin_nontemporal_store(o, reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(p.Y) + qoff));
     }
   }
 }

@@ -34,7 +34,7 @@ struct Row8;
 template <>
 struct Row8<uint16_t> {  // 8 bf16 = 16 bytes
   static __device__ __forceinline__ void load(const uint16_t* p, float* x) {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));  // streamed once
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       x[2 * j] = bf16lo(v[j]);
@@ -45,7 +45,7 @@ struct Row8<uint16_t> {  // 8 bf16 = 16 bytes
     u32x4 v;
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = pack_bf16(x[2 * j], x[2 * j + 1]);
-    *reinterpret_cast<u32x4*>(p) = v;
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
   }
 };
 
