@@ -343,6 +343,13 @@ def main():
         sampled8k = torch.empty((1, 1, 8192), device=dev, dtype=torch.int32)
         _, sp8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k), 10, 2)
         other.update({"sample_perm_n32768_ms": sp_ms, "sample_perm_n8192_ms": sp8_ms})
+        # the same permutations through the bucketed O(n) path (needs a workspace)
+        wss = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_SAMPLE_PERM), device=dev, dtype=torch.uint8)
+        _, spw_ms = time_op(lambda: sa.sa_sample_perm(desc, 1, 0, sampled, wss), 10, 2)
+        wss8 = torch.empty(sa.sa_workspace_bytes(d8k, sa.SA_OP_SAMPLE_PERM), device=dev, dtype=torch.uint8)
+        _, spw8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k, wss8), 10, 2)
+        other.update({"sample_perm_ws_n32768_ms": spw_ms, "sample_perm_ws_n8192_ms": spw8_ms})
+        del wss, wss8
         # RoPE on original positions for Q and K of the headline shape (out of place; table built once)
         table = torch.empty((wl.n, wl.d // 2, 2), device=dev, dtype=torch.float32)
         sa.sa_rope_table(wl.n, wl.d, 1e6, 0, table)

@@ -74,7 +74,8 @@ typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BW
                SA_OP_CHECK_PERM = 4,
                SA_OP_GATE_PROJ_BWD = 5,        /* sa_gate_proj_bwd, both branches */
                SA_OP_GATE_PROJ_BWD_SINGLE = 6, /* sa_gate_proj_bwd, single path   */
-               SA_OP_DUAL_PATH_BWD = 7         /* sa_dual_path_bwd                */
+               SA_OP_DUAL_PATH_BWD = 7,        /* sa_dual_path_bwd                */
+               SA_OP_SAMPLE_PERM = 8           /* sa_sample_perm, O(n) path       */
 } sa_op;
 
 const char* sa_status_string(sa_status s);
@@ -100,10 +101,14 @@ sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* 
  *   stream = mix(mix(seed) + G*((layer << 32) | s)),  r(p) = mix(stream + G*(p+1)),  G = 0x9E3779B97F4A7C15,
  * mix = the SplitMix64 output function; the sort key of slot p is r(p) with its low 20 bits replaced
  * by p (44 random bits, ties - probability < n^2/2^45 per slice - go to the smaller p), and perm = the
- * argsort of the keys.  Deterministic in (seed, layer, slice, n); O(n^2) compares per slice, no
- * workspace, no host round trip.  layer >= 0; n <= 2^20 (SA_ERR_UNSUPPORTED beyond); at most 65535
- * slices. */
-sa_status sa_sample_perm(const sa_desc* desc, uint64_t seed, int32_t layer, int32_t* perm, void* stream);
+ * argsort of the keys.  Deterministic in (seed, layer, slice, n); no host round trip.  layer >= 0;
+ * n <= 2^20 (SA_ERR_UNSUPPORTED beyond); at most 65535 slices.
+ * ws = NULL: the rank of every key is counted against all keys, O(n^2) compares per slice, no workspace.
+ * ws = sa_workspace_bytes(desc, SA_OP_SAMPLE_PERM) bytes of device memory: the keys are first spread over
+ * buckets by their top bits and ranked inside their bucket, O(n) work in five small launches (taken for
+ * n >= 16384, where it is the faster one); the same permutation, bit for bit. */
+sa_status sa_sample_perm(const sa_desc* desc, uint64_t seed, int32_t layer, int32_t* perm, void* ws,
+                         size_t ws_bytes, void* stream);
 
 /* Measurement helper: the gather and the scatter of Alg. 1 (Sec. 3.3, the two index operations around
  * the attention) with no attention in between.  For every (b, hq, slot p), with i = perm[p]:

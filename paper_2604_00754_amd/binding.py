@@ -15,7 +15,7 @@ SA_OK, SA_ERR_NULL, SA_ERR_SHAPE, SA_ERR_UNSUPPORTED, SA_ERR_WORKSPACE, SA_ERR_B
 SA_BF16, SA_F32 = 0, 1
 SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
-SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD = 5, 6, 7
+SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD, SA_OP_SAMPLE_PERM = 5, 6, 7, 8
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
@@ -59,7 +59,7 @@ def _load():
     lib.sa_gate_proj_bwd.restype = C.c_int
     lib.sa_gate_proj_bwd.argtypes = [dp] + [vp] * 12 + [sz, vp]
     lib.sa_sample_perm.restype = C.c_int
-    lib.sa_sample_perm.argtypes = [dp, C.c_uint64, C.c_int32, ip, vp]
+    lib.sa_sample_perm.argtypes = [dp, C.c_uint64, C.c_int32, ip, vp, sz, vp]
     lib.sa_dual_path_fwd.restype = C.c_int
     lib.sa_dual_path_fwd.argtypes = [dp, dp, vp, vp, vp, ip] + [vp] * 10
     lib.sa_dual_path_bwd.restype = C.c_int
@@ -122,9 +122,10 @@ def sa_fwd(desc, Q, K, V, perm, Y, LSE=None):
                        None, 0, _stream()), "sa_fwd")
 
 
-def sa_sample_perm(desc, seed, layer, perm):
+def sa_sample_perm(desc, seed, layer, perm, ws=None):
     _check(_lib.sa_sample_perm(C.byref(desc), C.c_uint64(int(seed) & (2 ** 64 - 1)), int(layer), _ptr(perm),
-                               _stream()), "sa_sample_perm")
+                               _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0, _stream()),
+           "sa_sample_perm")
 
 
 def sa_permuted_copy(desc, Q, K, V, perm, Y):

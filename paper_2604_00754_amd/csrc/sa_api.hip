@@ -155,6 +155,7 @@ size_t sa_workspace_bytes(const sa_desc* c, int op) {
     case SA_OP_GATE_PROJ_BWD: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, true);
     case SA_OP_GATE_PROJ_BWD_SINGLE: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, false);
     case SA_OP_DUAL_PATH_BWD: return dual_bwd_workspace(c).total;
+    case SA_OP_SAMPLE_PERM: return sa::sample_perm_workspace_bytes(c->perm_B * c->perm_H, c->n);
     default: return 0;
   }
 }
@@ -190,13 +191,16 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   return hip_status(run_fwd(c, p, (hipStream_t)stream));
 }
 
-sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t* perm, void* stream) {
+sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t* perm, void* ws, size_t ws_bytes,
+                         void* stream) {
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!perm) return SA_ERR_NULL;
   if (layer < 0) return SA_ERR_SHAPE;
   if (c->n > (1 << 20)) return SA_ERR_UNSUPPORTED;
-  return hip_status(sa::launch_sample_perm(perm, c->perm_B * c->perm_H, c->n, seed, layer, (hipStream_t)stream));
+  const int slices = c->perm_B * c->perm_H;
+  if (ws && ws_bytes < sa::sample_perm_workspace_bytes(slices, c->n)) return SA_ERR_WORKSPACE;
+  return hip_status(sa::launch_sample_perm(perm, slices, c->n, seed, layer, ws, (hipStream_t)stream));
 }
 
 sa_status sa_fwd_rope(const sa_desc* c, const void* Q, const void* K, const void* V, const int32_t* perm,

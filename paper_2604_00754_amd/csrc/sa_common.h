@@ -64,7 +64,9 @@ hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st);
 hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st);
 
 hipError_t launch_permuted_copy_bf16(const Pass& p, hipStream_t st);
-hipError_t launch_sample_perm(int32_t* perm, int slices, int n, uint64_t seed, int layer, hipStream_t st);
+// ws = nullptr: O(n^2) rank counting, no workspace; otherwise sample_perm_workspace_bytes(slices, n) bytes
+hipError_t launch_sample_perm(int32_t* perm, int slices, int n, uint64_t seed, int layer, void* ws, hipStream_t st);
+size_t sample_perm_workspace_bytes(int slices, int n);
 // Eq. 6 + Eq. 5 (sa_gate_proj.hip); Y_swa = W_swa = nullptr selects the single-path gate
 hipError_t launch_gate_proj_fwd_bf16(int B, int Hq, int n, int d, const void* Y_sa, const void* Y_swa,
                                      const void* W_sa, const void* W_swa, void* Y, void* G_sa, void* G_swa,

@@ -134,6 +134,79 @@ __global__ __launch_bounds__(256) void sample_perm_kernel(int32_t* __restrict__ 
   if (sub == 0 && p < n) perm[(size_t)slice * n + rank] = p;
 }
 
+// ---- the same permutation in O(n) work, with a workspace: the keys are uniform 64-bit numbers, so their
+// top bits spread them evenly over NB buckets (64 keys each on average).  Count per bucket, exclusive scan,
+// scatter the keys into their buckets (in any order), then rank every key inside its bucket: the slot of
+// key k goes to perm[start(bucket) + #{keys of the bucket below k}].  The result does not depend on the
+// order in which the atomic counters hand out places.
+__device__ __forceinline__ uint64_t slice_stream(uint64_t seed, int layer, int slice) {
+  return splitmix_mix(splitmix_mix(seed) + kGamma * (((uint64_t)(uint32_t)layer << 32) | (uint32_t)slice));
+}
+
+struct SampleWs {
+  uint64_t* keys;  // [slices][n]
+  int* count;      // [slices][NB]
+  int* cursor;     // [slices][NB]: first free place of the bucket while scattering, its end afterwards
+  int NB, shift;   // bucket of key k = k >> shift (shift = 64: one bucket)
+};
+
+__device__ __forceinline__ int bucket_of(uint64_t k, int shift) { return shift >= 64 ? 0 : (int)(k >> shift); }
+
+__global__ __launch_bounds__(256) void sample_count_kernel(SampleWs w, const int n, const uint64_t seed, const int layer) {
+  const int slice = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= n) return;
+  const uint64_t k = sort_key(slice_stream(seed, layer, slice), p);
+  atomicAdd(w.count + (size_t)slice * w.NB + bucket_of(k, w.shift), 1);
+}
+
+// one workgroup per slice: cursor = exclusive prefix sum of count
+__global__ __launch_bounds__(256) void sample_scan_kernel(SampleWs w) {
+  __shared__ int part[256];
+  const int slice = blockIdx.x, t = threadIdx.x;
+  const int* cnt = w.count + (size_t)slice * w.NB;
+  int* cur = w.cursor + (size_t)slice * w.NB;
+  const int per = (w.NB + 255) / 256, b0 = t * per, b1 = min(b0 + per, w.NB);
+  int sum = 0;
+  for (int b = b0; b < b1; ++b) sum += cnt[b];
+  part[t] = sum;
+  __syncthreads();
+  if (t == 0) {
+    int run = 0;
+    for (int i = 0; i < 256; ++i) {
+      const int v = part[i];
+      part[i] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  int run = part[t];
+  for (int b = b0; b < b1; ++b) {
+    cur[b] = run;
+    run += cnt[b];
+  }
+}
+
+__global__ __launch_bounds__(256) void sample_scatter_kernel(SampleWs w, const int n, const uint64_t seed, const int layer) {
+  const int slice = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= n) return;
+  const uint64_t k = sort_key(slice_stream(seed, layer, slice), p);
+  const int place = atomicAdd(w.cursor + (size_t)slice * w.NB + bucket_of(k, w.shift), 1);
+  w.keys[(size_t)slice * n + place] = k;
+}
+
+__global__ __launch_bounds__(256) void sample_rank_kernel(SampleWs w, int32_t* __restrict__ perm, const int n) {
+  const int slice = blockIdx.y, e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= n) return;
+  const uint64_t* keys = w.keys + (size_t)slice * n;
+  const uint64_t k = keys[e];
+  const int b = bucket_of(k, w.shift);
+  const int cnt = w.count[(size_t)slice * w.NB + b];
+  const int start = w.cursor[(size_t)slice * w.NB + b] - cnt;  // the cursor ended at the bucket's end
+  int rank = 0;
+  for (int j = 0; j < cnt; ++j) rank += keys[start + j] < k ? 1 : 0;
+  perm[(size_t)slice * n + start + rank] = (int32_t)(k & kIndexMask);
+}
+
 template <int LPR>  // lanes per row, each lane owns 16 bytes of the row
 __device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
@@ -276,9 +349,42 @@ hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, 
   return hipGetLastError();
 }
 
-hipError_t launch_sample_perm(int32_t* perm, int slices, int n, uint64_t seed, int layer, hipStream_t st) {
+// buckets for the workspace path: a power of two, 64 keys per bucket on average
+static int sample_buckets(int n) {
+  int nb = 1;
+  while ((long)nb * 64 < n) nb *= 2;
+  return nb;
+}
+
+size_t sample_perm_workspace_bytes(int slices, int n) {
+  const size_t nb = (size_t)sample_buckets(n);
+  return (size_t)slices * ((size_t)n * 8 + 2 * nb * 4) + 512;
+}
+
+hipError_t launch_sample_perm(int32_t* perm, int slices, int n, uint64_t seed, int layer, void* ws, hipStream_t st) {
   if (!perm || slices < 1 || slices > 65535 || n < 1) return hipErrorInvalidValue;
   if (n > (1 << 20)) return hipErrorNotSupported;  // the slot index takes the low 20 bits of the sort key
+  // five small launches: below ~16K slots the single O(n^2) launch is faster (0.017 against 0.037 ms at
+  // n = 8192; 0.135 against 0.045 ms at n = 32768)
+  if (ws && n >= 16384) {
+    SampleWs w;
+    w.NB = sample_buckets(n);
+    int bits = 0;
+    while ((1 << bits) < w.NB) ++bits;
+    w.shift = 64 - bits;
+    char* base = reinterpret_cast<char*>((reinterpret_cast<uintptr_t>(ws) + 255) & ~(uintptr_t)255);
+    w.keys = reinterpret_cast<uint64_t*>(base);
+    w.count = reinterpret_cast<int*>(base + (size_t)slices * n * 8);
+    w.cursor = w.count + (size_t)slices * w.NB;
+    hipError_t e = launch_fill_zero(w.count, (size_t)slices * w.NB * 4, st);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)((n + 255) / 256), (unsigned)slices);
+    hipLaunchKernelGGL(sample_count_kernel, grid, dim3(256), 0, st, w, n, seed, layer);
+    hipLaunchKernelGGL(sample_scan_kernel, dim3((unsigned)slices), dim3(256), 0, st, w);
+    hipLaunchKernelGGL(sample_scatter_kernel, grid, dim3(256), 0, st, w, n, seed, layer);
+    hipLaunchKernelGGL(sample_rank_kernel, grid, dim3(256), 0, st, w, perm, n);
+    return hipGetLastError();
+  }
   const int per_block = 256 / SAMPLE_LPP;
   hipLaunchKernelGGL(sample_perm_kernel, dim3((unsigned)((n + per_block - 1) / per_block), (unsigned)slices), dim3(256), 0, st,
                      perm, n, seed, layer);
