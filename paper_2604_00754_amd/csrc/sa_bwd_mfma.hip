@@ -58,14 +58,6 @@ struct Cfg {
   static_assert(BN <= NT && BN % 32 == 0 && NV >= 1, "one thread per streamed slot for the per-slot values");
 };
 
-// LDS exchange inside one wave (a wave's LDS instructions execute in order): only the compiler has to
-// be kept from moving the reads above the writes.
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Accumulator i = 4*mq + x of lane group g2 holds tile row 32*kb + 8*mq + 4*g2 + x.  Position of tile
 // row r in "accumulator order": the 16 rows of one (kb, g2) are contiguous, in the order of i.
 __device__ __forceinline__ int acc_order_pos(int r) {

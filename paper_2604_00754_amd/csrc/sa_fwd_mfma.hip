@@ -466,7 +466,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
         w[1] = pack_bf16(acc[db][4 * mq + 2], acc[db][4 * mq + 3]);
         *reinterpret_cast<u32x2*>(Os + c32 * C::KSTR + 32 * db + 8 * mq + 4 * g2) = w;
       }
-    __syncthreads();
+    wave_lds_sync();  // the staging rows are this wave's own
     int dst[NP];
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) dst[pass] = rowstash[wave * 32 + pass * C::WRPP + lane / C::VPR];

@@ -66,6 +66,14 @@ __device__ __forceinline__ void store_transposed_4x8(bf16_t* dst, int tstr, cons
   }
 }
 
+// LDS exchange inside one wave (a wave's LDS instructions execute in order): only the compiler has to
+// be kept from moving the reads above the writes.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // XCD-aware work index: every XCD gets one contiguous chunk of the work list, so that neighbours
 // in the list (which share K/V or Q/dO rows) meet in the same L2.  Returns -1 for surplus blocks.
 __device__ __forceinline__ long xcd_work_index(long total_work) {
