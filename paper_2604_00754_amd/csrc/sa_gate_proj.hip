@@ -103,6 +103,31 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
 #pragma unroll
       for (int i = 0; i < 16; ++i) out[fi][ti][i] = 0.f;
 
+  // Output rows leave through a wave-private LDS area: the accumulator layout gives a lane 8-byte pieces of
+  // 32 different rows, the staged copy lets 8 lanes write one full 128-byte piece of a row (non-temporal:
+  // the outputs are written once).  stage_out is called after a workgroup barrier (the area overlays the
+  // GEMM buffers).
+  constexpr int OSTR = 64 + 8;  // bf16 per staged row (64 features of one token + 16 B pad)
+  bf16_t* ostage = reinterpret_cast<bf16_t*>(smem) + wave * 64 * OSTR;
+  auto stage_put = [&](int fi, int ti, int q, u32x2 w) {
+    *reinterpret_cast<u32x2*>(ostage + (32 * ti + c32) * OSTR + 32 * fi + 8 * q + 4 * g2) = w;
+  };
+  auto stage_flush = [&](bf16_t* dst) {
+    wave_lds_sync();
+    const int o = o0 + 64 * wn;  // first of the wave's 64 features: inside one head
+    const size_t col = (size_t)(o % D) + (lane & 7) * 8;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int tl = pass * 8 + (lane >> 3);
+      const int token = i0 + 64 * wm + tl;
+      if (token < n) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(ostage + tl * OSTR + (lane & 7) * 8);
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + (((size_t)b * H + o / D) * n + token) * D + col));
+      }
+    }
+    wave_lds_sync();
+  };
+
   const int branches = p.Y_x[1] ? 2 : 1;
   for (int x = 0; x < branches; ++x) {
     const bf16_t* Yx = reinterpret_cast<const bf16_t*>(p.Y_x[x]);
@@ -147,6 +172,7 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
     bf16_t* Gx = reinterpret_cast<bf16_t*>(p.G_x[x]);
     const bf16_t* E1 = reinterpret_cast<const bf16_t*>(p.E1);
     const bf16_t* E2 = reinterpret_cast<const bf16_t*>(p.E2);
+    if (MODE == GP_FORWARD && Gx) __syncthreads();  // every wave has read its last operands: the area is free
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       const int token = i0 + 64 * wm + 32 * ti + c32;
@@ -167,11 +193,11 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
               gv[e] = sigmoidf_exact(acc[fi][ti][4 * q + e]);
               out[fi][ti][4 * q + e] = fmaf(gv[e], yv[e], out[fi][ti][4 * q + e]);
             }
-            if (Gx && live) {
+            if (Gx) {
               u32x2 w;
               w[0] = pack_bf16(gv[0], gv[1]);
               w[1] = pack_bf16(gv[2], gv[3]);
-              *reinterpret_cast<u32x2*>(Gx + at) = w;
+              stage_put(fi, ti, q, w);
             }
           } else {
             const u32x2 a = *reinterpret_cast<const u32x2*>(E1 + at), c = *reinterpret_cast<const u32x2*>(E2 + at);
@@ -182,25 +208,22 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
           }
         }
     }
+    if (MODE == GP_FORWARD && Gx) stage_flush(Gx);
   }
 
-  bf16_t* Yo = reinterpret_cast<bf16_t*>(p.Y);
+  __syncthreads();  // every wave has read its last operands (or flushed its last gate rows): the area is free
 #pragma unroll
-  for (int ti = 0; ti < 2; ++ti) {
-    const int token = i0 + 64 * wm + 32 * ti + c32;
-    if (token >= n) continue;
+  for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
     for (int fi = 0; fi < 2; ++fi)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int o = o0 + 64 * wn + 32 * fi + 8 * q + 4 * g2;
-        const size_t at = (((size_t)b * H + o / D) * n + token) * D + o % D;
         u32x2 w;
         w[0] = pack_bf16(out[fi][ti][4 * q + 0], out[fi][ti][4 * q + 1]);
         w[1] = pack_bf16(out[fi][ti][4 * q + 2], out[fi][ti][4 * q + 3]);
-        *reinterpret_cast<u32x2*>(Yo + at) = w;
+        stage_put(fi, ti, q, w);
       }
-  }
+  stage_flush(reinterpret_cast<bf16_t*>(p.Y));
 }
 
 
