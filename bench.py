@@ -55,7 +55,8 @@ def time_op(fn, steps, warmup):
 def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
     """Flop of the matrix instructions the forward kernel issues at this shape (symmetric circular
     window): per wave (32 query slots) every 32-key block of the workgroup's tiles that any of its
-    queries can see, each costing 2 * (d/16) MFMAs of 32x32x16."""
+    queries can see, each costing 2 * (d/16) MFMAs of 32x32x16.  BM = query slots of a workgroup (128, or
+    64 / 32 when it takes 2 / 4 query heads of a KV group over the same slots)."""
     h = (w - 1) // 2
     L, R = min(h, (n - 1) // 2), 0
     R = min(h, n - 1 - L)
@@ -75,6 +76,15 @@ def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
                 if not (dmax < -L or dmin > R) and tb0 <= t_hi:
                     total_blocks += 1
     return float(total_blocks) * per_block * B * Hq
+
+
+def heads_per_workgroup(wl):
+    """Query heads of a KV group that one workgroup of the forward kernel takes (over the same slots) when
+    they share a permutation: 4, 2 or 1 by group size; 1 with per-head permutations."""
+    g = wl.Hq // wl.Hkv
+    if wl.perm_H != 1:
+        return 1
+    return 4 if g % 4 == 0 else (2 if g % 2 == 0 else 1)
 
 
 def cpu_baseline(wl, Q, K, V, perm, rows_per_head):
@@ -288,7 +298,7 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
                 "median_launch_ms": float(np.median(launch_samples)), "min_launch_ms": float(np.min(launch_samples)),
-                "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq),
+                "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq, BM=128 // heads_per_workgroup(wl)),
                 "caches": "not flushed between launches (see other_ops.cold_cache_ms)"}
     gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
     roofline_hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",

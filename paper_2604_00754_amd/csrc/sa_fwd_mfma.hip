@@ -1,7 +1,12 @@
 // bf16 forward of Stochastic Attention on gfx950 matrix cores.
 //
-// One workgroup (4 wavefronts) owns 128 consecutive PERMUTED slots of one (batch, query head); a
-// wavefront owns 32 of them.  The workgroup walks the slots of the window band (Eq. 3) in tiles of
+// One workgroup (4 wavefronts) owns 128 query rows of one (batch, KV head); a wavefront owns 32
+// consecutive PERMUTED slots of one query head.  Without grouped heads the four wavefronts take four
+// adjacent 32-slot blocks of the same query head.  When the query heads of a KV group share one
+// permutation (App. A: one permutation per layer), the wavefronts instead take the SAME slots of up
+// to four query heads of the group: all of them then need exactly the same K/V rows, so the band the
+// workgroup walks is 32 + w slots instead of 128 + w and no wavefront idles on tiles outside its own
+// band.  The workgroup walks the slots of the window band (Eq. 3) in tiles of
 // 64; K and V rows of a tile are read through the index tensor straight from their original
 // positions (the permuted copies of Alg. 1 never exist), staged in LDS (double buffered, one
 // barrier per tile), and consumed by
@@ -22,7 +27,7 @@
 namespace sa {
 namespace {
 
-constexpr int BM = 128;  // query slots per workgroup
+constexpr int BM = 128;  // query rows per workgroup (slots x heads)
 constexpr int BN = 64;   // key slots per tile
 constexpr int NT = 256;  // threads per workgroup
 
@@ -76,23 +81,27 @@ enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 
 // PERM = false: identity permutation (plain windowed attention); no index loads are generated.
 template <int D, bool PERM, int CAUSAL>
-__global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
+__global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+                                                              const int hshift) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
 
-  // work list order: the query heads of a group, then the next query tile -- neighbours share K/V rows
+  // 1 << hshift = query heads per workgroup (1, 2 or 4; a divisor of the group size).  Work list order: the
+  // head sets of a KV group, then the next query tile -- neighbours share K/V rows
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
-  const int hg = (int)(work % p.g);
-  long rest = work / p.g;
+  const int sets = p.g >> hshift;
+  const int hset = (int)(work % sets);
+  long rest = work / sets;
   const int qt = (int)(rest % num_qt);
   rest /= num_qt;
   const int hk = (int)(rest % p.Hkv);
   const int b = (int)(rest / p.Hkv);
-  const int hq = hk * p.g + hg;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
+  const int hq = hk * p.g + (hset << hshift) + (wave & ((1 << hshift) - 1));  // this wave's query head
+  const int bm = BM >> hshift;                                               // query slots of the workgroup
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
   const bool circular = p.win.circular != 0;
@@ -103,9 +112,9 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const bf16_t* __restrict__ Kh = reinterpret_cast<const bf16_t*>(p.K) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   const bf16_t* __restrict__ Vh = reinterpret_cast<const bf16_t*>(p.V) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
 
-  const int p0 = qt * BM;
-  const int q_last = min(p0 + BM - 1, n - 1);
-  const int s_w0 = p0 + 32 * wave;  // first query slot of this wave
+  const int p0 = qt * bm;
+  const int q_last = min(p0 + bm - 1, n - 1);
+  const int s_w0 = p0 + 32 * (wave >> hshift);  // first query slot of this wave
   const int s = s_w0 + c32;         // this lane's query slot (column of S^T)
   const int orig_q = orig_of(min(s, n - 1));
 
@@ -511,8 +520,12 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
 
 template <int D>
 hipError_t launch_t(const Pass& p, hipStream_t st) {
-  const int num_qt = (p.n + BM - 1) / BM;
-  const long total = (long)num_qt * p.Hq * p.B;
+  // Query heads of a KV group that read K/V through the same permutation (or none) share a workgroup
+  const bool shared_perm = !p.perm || p.perm_H == 1;
+  const int hshift = !shared_perm ? 0 : (p.g % 4 == 0 ? 2 : (p.g % 2 == 0 ? 1 : 0));
+  const int bm = BM >> hshift;
+  const int num_qt = (p.n + bm - 1) / bm;
+  const long total = (long)num_qt * (p.Hq >> hshift) * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks), block(NT);
@@ -521,7 +534,7 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
   const bool window_is_causal = !p.perm && !p.win.circular && p.win.R == 0;
   const int mode = (!p.causal || window_is_causal) ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
 #define SA_LAUNCH_FWD(PERM_, MODE_) \
-  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_>), grid, block, 0, st, p, num_qt, total)
+  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_>), grid, block, 0, st, p, num_qt, total, hshift)
   if (p.perm) {
     if (mode == CAUSAL_NONE) SA_LAUNCH_FWD(true, CAUSAL_NONE);
     else if (mode == CAUSAL_I16) SA_LAUNCH_FWD(true, CAUSAL_I16);

@@ -82,6 +82,18 @@ def test_bf16_gqa_shared_and_per_batch_perm():
     run_fwd(2, 8, 2, 600, 64, 256, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=41)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 2), (16, 2), (6, 2), (3, 1), (12, 2)])
+def test_bf16_query_heads_of_a_group_share_a_workgroup(Hq, Hkv):
+    """One permutation for all heads (or none): the query heads of a KV group are processed 4, 2 or 1 at
+    a time over the same slots, by group size (4, 2, 8, 3, 3 and 6 here).  Ragged n (not a multiple of 32),
+    each window kind, d = 64 and 128; per-head permutations keep one head per workgroup."""
+    run_fwd(1, Hq, Hkv, 555, 128, 128, CIRC, 1, "bf16", seed=60 + Hq)
+    run_fwd(2, Hq, Hkv, 300, 64, 70, LIN, 0, "bf16", perm_B=2, seed=61 + Hq)
+    run_fwd(1, Hq, Hkv, 421, 64, 64, ONE, 1, "bf16", identity=True, use_swa_entry=True, seed=62 + Hq)
+    run_fwd(1, Hq, Hkv, 333, 128, 500, CIRC, 1, "bf16", perm_H=Hq, seed=63 + Hq)   # window covers the ring
+    run_fwd(1, Hq, Hkv, 31, 64, 8, CIRC, 1, "bf16", seed=64 + Hq)                  # less than one wave of slots
+
+
 def test_bf16_later_keys_dominate():
     """Scores of later (causally masked) keys far above the visible ones: the packed 16-bit mask clears
     their probabilities after the exponential, so they must neither move the softmax reference nor leak
