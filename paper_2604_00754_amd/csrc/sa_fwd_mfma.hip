@@ -360,7 +360,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_with_other_half(mx);
     if (__any(mx > m_ref + lazy)) {  // (-inf + lazy = -inf: the first visible key always triggers)
       if (CAUSAL == CAUSAL_I16) {
         // mx still counts later keys (their probabilities are cleared further down, whatever they
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
 #pragma unroll
           for (int i = 0; i < 16; ++i) mv = fmaxf(mv, t[i]);
         }
-        mx = fmaxf(mv, __shfl_xor(mv, 32));
+        mx = max_with_other_half(mv);
       }
       const float m_new = fmaxf(m_ref, mx);
       const float alpha = (mx > m_ref + lazy) ? __builtin_amdgcn_exp2f((m_ref - m_new) * cs) : 1.f;
@@ -442,7 +442,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   }
 
   // ---- epilogue: normalise, transpose through LDS, scatter rows to their original positions
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = sum_with_other_half(l_run);
   const float inv_l = 1.f / l_tot;
   const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
   const size_t my_row = head_row0 + orig_q;  // this lane's output row (valid when s < n)

@@ -74,6 +74,28 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The value lane^32 holds, without a trip through LDS: v_permlane32_swap_b32 exchanges the upper 32 lanes
+// of its first operand with the lower 32 lanes of its second.  Fed two copies of x it leaves the lower
+// half's values in both halves of the first register and the upper half's in both halves of the second.
+// Written as an instruction: the compiler's builtin for it returns the first register for both results.
+// The no-op covers the wait states the instruction needs after a vector write of its operands.
+__device__ __forceinline__ void both_halves(float x, float* lo, float* hi) {
+  float a = x, b = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  *lo = a;  // x of lane (l & 31)
+  *hi = b;  // x of lane (l & 31) + 32
+}
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float lo, hi;
+  both_halves(x, &lo, &hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  float lo, hi;
+  both_halves(x, &lo, &hi);
+  return lo + hi;
+}
+
 // XCD-aware work index: every XCD gets one contiguous chunk of the work list, so that neighbours
 // in the list (which share K/V or Q/dO rows) meet in the same L2.  Returns -1 for surplus blocks.
 __device__ __forceinline__ long xcd_work_index(long total_work) {
