@@ -8,15 +8,16 @@
 // workgroup walks is 32 + w slots instead of 128 + w and no wavefront idles on tiles outside its own
 // band.  The workgroup walks the slots of the window band (Eq. 3) in tiles of
 // 64; K and V rows of a tile are read through the index tensor straight from their original
-// positions (the permuted copies of Alg. 1 never exist), staged in LDS (double buffered, one
+// positions (the permuted copies of Alg. 1 never exist) by direct global-to-LDS loads, one tile ahead
+// (no registers, no LDS stores; rows unpadded, 16-byte chunks XOR-swizzled; double buffered, one
 // barrier per tile), and consumed by
 //   S^T = K Q^T          (v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in registers)
 //   mask: window on slot offsets, causal test on original positions (Sec. 3.3, App. B)
 //   online softmax (Eq. 1) -- in the S^T layout a lane holds one query column, so row statistics
 //   are lane-local up to one exchange with lane^32; the running maximum is only moved when a tile
 //   exceeds it by more than 2^8, which leaves the normalised result unchanged
-//   O^T += V^T P^T       (A = V^T from LDS, stored transposed by the loader so that the reads are
-//                         plain 16-byte ones; B = P^T taken directly from the S^T accumulators)
+//   O^T += V^T P^T       (A = V^T gathered from the row-major V tile by transposing LDS reads,
+//                         ds_read_b64_tr_b16; B = P^T taken directly from the S^T accumulators)
 // The epilogue normalises, transposes through LDS and writes each row to its ORIGINAL position
 // (the "undo permute" of Alg. 1), optionally forming the gated sum of Eq. 5 on the way out.
 #include <type_traits>
@@ -33,30 +34,40 @@ constexpr int NT = 256;  // threads per workgroup
 
 template <int D>
 struct Cfg {
-  static constexpr int KSTR = D + 8;     // bf16 per K row in LDS: +16 B keeps 16 consecutive rows on distinct banks for 16-byte reads
-  static constexpr int VTSTR = BN + 8;   // bf16 per V^T row (one d, 64 key slots) in LDS, same padding rule
-  static constexpr int VPR = D / 8;      // 16-byte vectors per K/V row
-  static constexpr int RPP = NT / VPR;   // K rows covered by one pass of the workgroup
-  static constexpr int NV = BN / RPP;    // K vectors per thread per tile
-  static constexpr int VUNITS = 16 * VPR;  // V work units: (group of 4 key rows) x (16-byte chunk)
-  static constexpr int WRPP = 64 / VPR;  // rows covered by one pass of a single wave
-  static constexpr int KBYTES = BN * KSTR * 2;
-  static constexpr int VBYTES = D * VTSTR * 2;
-  static constexpr int BUF_BYTES = KBYTES + VBYTES;  // K | V^T
-  static constexpr int QBYTES = 4 * 32 * KSTR * 2;   // per-wave Q / O staging, aliases one buffer
+  static constexpr int QSTR = D + 8;     // bf16 per row of the Q / O staging area: +16 B keeps 16 consecutive rows on distinct banks for 16-byte reads
+  static constexpr int CPR = D / 8;      // 16-byte chunks per K/V row
+  static constexpr int RPI = 64 / CPR;   // K/V rows one wave moves with one 16-byte-per-lane instruction
+  static constexpr int NI = BN / (4 * RPI);  // such instructions per wave, tile and operand
+  static constexpr int WRPP = 64 / CPR;  // rows covered by one pass of a single wave
+  static constexpr int TILE_BYTES = BN * D * 2;      // one operand tile, rows unpadded
+  static constexpr int BUF_BYTES = 2 * TILE_BYTES;   // K | V
+  static constexpr int QBYTES = 4 * 32 * QSTR * 2;   // per-wave Q / O staging; starts at a buffer and runs past its end
   static constexpr int RING = 4;                     // tiles whose row indices are kept in LDS
-  static constexpr int LDS_BYTES = 2 * BUF_BYTES + RING * BN * 6 + BM * 4;  // buffers | index ring | 16-bit index ring | row stash
-  static_assert(QBYTES <= BUF_BYTES, "staging must fit in one buffer");
-  static_assert(VUNITS <= NT, "one V unit per thread at most");
-  static_assert(BUF_BYTES % 16 == 0, "buffers stay 16-byte aligned");
+  static constexpr int RING_OFF = BUF_BYTES + QBYTES;  // buffer 0 | buffer 1 = start of the staging area | its overhang
+  static constexpr int LDS_BYTES = RING_OFF + RING * BN * 6 + BM * 4;  // ... | index ring | 16-bit index ring | row stash
+  static_assert(QBYTES >= BUF_BYTES, "the staging area covers buffer 1");
+  static_assert(BUF_BYTES % 16 == 0 && QBYTES % 16 == 0, "everything stays 16-byte aligned");
 };
 
-// Position of key row k (0..63) inside a V^T row.  Accumulator i = 8c + 4h + x of lane group g holds
-// tile row 32kb + 16c + 8h + 4g + x; storing it at 32kb + 16c + 8g + 4h + x makes the 8 values a
-// lane needs for MFMA step (kb, c) one contiguous 16-byte read.
-__device__ __forceinline__ int vt_pos4(int u) {  // u = k / 4 -> position / 4
-  return (u & 12) | ((u & 1) << 1) | ((u & 2) >> 1);
+// K and V tiles lie in LDS as they lie in memory (row after row, no padding: that is how the direct
+// global-to-LDS loads deliver them), with the 16-byte chunks of a row permuted by an XOR with swz(row)
+// so that the two read patterns are conflict-free: 16 rows x the same chunk (K operand, ds_read_b128)
+// and 4 rows x 4 consecutive chunks (V operand, transposing 8-byte reads).
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
+
+// 16 bytes per lane from global memory (scalar base + 32-bit lane offset) straight into LDS at
+// lds_byte_addr + 16 * lane.  The address travels in M0 and must be wave-uniform.  The compiler does not
+// see this load: it is waited for with an explicit s_waitcnt vmcnt(0) before the barrier that publishes
+// the tile.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_byte_offset, uint32_t lds_byte_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_byte_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(lane_byte_offset), "s"(base)
+               : "memory");
+}
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 
 // 16-byte chunk `chunk` of row `row` of a [n, D] bf16 head: a 32-bit byte offset from the (wave-uniform)
 // head pointer, so the address needs one vector instruction (the host checks n * D * 2 < 2^31).
@@ -127,22 +138,22 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const int ntiles = (t_hi - t_lo + BN) / BN;
 
   // ---- original indices of the rows of tiles 0..2 go to the LDS ring; tile 3's stay in a register
-  int* ring = reinterpret_cast<int*>(smem + 2 * C::BUF_BYTES);
+  int* ring = reinterpret_cast<int*>(smem + C::RING_OFF);
   auto tile_row_orig = [&](int tile) -> int {  // original index of row `tid` of a tile (clamped to the range)
     return orig_of(wrap_slot(min(t_lo + tile * BN + tid, t_hi), n));
   };
   // CAUSAL_I16 keeps a second copy for the mask: index - 32768 as int16, ordered so that a lane's 16
   // accumulators of a block (key rows 8*(i/4) + 4*g2 + i%4) are 32 contiguous bytes
-  short* ring16 = reinterpret_cast<short*>(smem + 2 * C::BUF_BYTES + C::RING * BN * 4);
+  short* ring16 = reinterpret_cast<short*>(smem + C::RING_OFF + C::RING * BN * 4);
   const int pos16 = (tid & 32) | ((tid & 4) << 2) | ((tid >> 1) & 12) | (tid & 3);  // row tid -> (kb, g2, i)
   // ---- prologue.  All index loads first (this lane's query, the wave's query rows, the rows of tiles
   // 0..3); then, one memory round trip later, the Q rows and the K/V rows of tile 0 together.
   constexpr int NP = 32 / C::WRPP;
-  const int chunk16 = lane % C::VPR;
+  const int chunk16 = lane % C::CPR;
   int src[NP];
 #pragma unroll
-  for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::VPR, n - 1));
-  int* rowstash = reinterpret_cast<int*>(smem + 2 * C::BUF_BYTES + C::RING * BN * 6);  // original index of the workgroup's 128 rows
+  for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::CPR, n - 1));
+  int* rowstash = reinterpret_cast<int*>(smem + C::RING_OFF + C::RING * BN * 6);  // original index of the workgroup's 128 rows
   int pk_reg = 0;
   if (tid < BN) {
     const int i0 = tile_row_orig(0), i1 = tile_row_orig(1), i2 = tile_row_orig(2);
@@ -158,72 +169,47 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   }
   if (chunk16 == 0) {
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) rowstash[wave * 32 + pass * C::WRPP + lane / C::VPR] = src[pass];
+    for (int pass = 0; pass < NP; ++pass) rowstash[wave * 32 + pass * C::WRPP + lane / C::CPR] = src[pass];
   }
   __syncthreads();  // ring visible
 
-  // ---- tile loader.  K: thread -> rows (v*RPP + tid/VPR), 16-byte chunk tid%VPR, stored row-major.
-  // V: thread -> 4 consecutive rows 4u..4u+3 (u = tid%16) and chunk tid/16, transposed in registers
-  // and stored as V^T (8 rows of 4 key slots each).  Row indices come from the LDS ring.
-  const int ld_row = tid / C::VPR, ld_chunk = tid % C::VPR;
-  const int vu = tid & 15, vdc = tid >> 4;
-  const bool v_thread = tid < C::VUNITS;
-  u32x4 kreg[C::NV], vreg[4];
-  auto load_rows = [&](int tile) {
+  // ---- tile loader: direct global-to-LDS loads, 16 bytes per lane.  One instruction of a wave fills RPI
+  // consecutive rows of the tile; lane l delivers physical chunk l % CPR of row l / CPR, i.e. fetches the
+  // logical chunk (l % CPR) ^ swz(row) of the row the index ring names.  The swizzle depends on the low
+  // four bits of the row only, which are the same for every instruction of the lane.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int ld_row = wave * C::RPI + lane / C::CPR;  // row of the lane in instruction 0
+  const uint32_t ld_chunk_off = (uint32_t)(((lane % C::CPR) ^ swz<D>(ld_row)) * 16);
+  auto load_tile = [&](const int tile, const int buf) {
     const int* idx = ring + (tile & (C::RING - 1)) * BN;
-    int kidx[C::NV];
+    int ridx[C::NI];
 #pragma unroll
-    for (int v = 0; v < C::NV; ++v) kidx[v] = idx[v * C::RPP + ld_row];
-    const int4 vidx = *reinterpret_cast<const int4*>(idx + 4 * vu);
+    for (int j = 0; j < C::NI; ++j) ridx[j] = idx[j * 4 * C::RPI + ld_row];
 #pragma unroll
-    for (int v = 0; v < C::NV; ++v)
-      kreg[v] = load_row_chunk<D>(Kh, kidx[v], ld_chunk);
-    if (v_thread) {
-      vreg[0] = load_row_chunk<D>(Vh, vidx.x, vdc);
-      vreg[1] = load_row_chunk<D>(Vh, vidx.y, vdc);
-      vreg[2] = load_row_chunk<D>(Vh, vidx.z, vdc);
-      vreg[3] = load_row_chunk<D>(Vh, vidx.w, vdc);
-    }
-  };
-  auto store_tile = [&](int buf) {
-    bf16_t* Ks = reinterpret_cast<bf16_t*>(smem + buf * C::BUF_BYTES);
-    bf16_t* Vt = reinterpret_cast<bf16_t*>(smem + buf * C::BUF_BYTES + C::KBYTES);
-#pragma unroll
-    for (int v = 0; v < C::NV; ++v)
-      *reinterpret_cast<u32x4*>(Ks + (v * C::RPP + ld_row) * C::KSTR + ld_chunk * 8) = kreg[v];
-    if (v_thread) {
-      bf16_t* dst = Vt + (8 * vdc) * C::VTSTR + 4 * vt_pos4(vu);
-#pragma unroll
-      for (int m = 0; m < 4; ++m) {  // dword m of each row holds d = 8*vdc + 2m, 2m+1
-        u32x2 lo, hi;
-        lo[0] = __builtin_amdgcn_perm(vreg[1][m], vreg[0][m], 0x05040100u);
-        lo[1] = __builtin_amdgcn_perm(vreg[3][m], vreg[2][m], 0x05040100u);
-        hi[0] = __builtin_amdgcn_perm(vreg[1][m], vreg[0][m], 0x07060302u);
-        hi[1] = __builtin_amdgcn_perm(vreg[3][m], vreg[2][m], 0x07060302u);
-        *reinterpret_cast<u32x2*>(dst + (2 * m) * C::VTSTR) = lo;
-        *reinterpret_cast<u32x2*>(dst + (2 * m + 1) * C::VTSTR) = hi;
-      }
+    for (int j = 0; j < C::NI; ++j) {
+      const uint32_t goff = (uint32_t)ridx[j] * (uint32_t)(D * 2) + ld_chunk_off;
+      const uint32_t dst = lds0 + buf * C::BUF_BYTES + (j * 4 * C::RPI + wave * C::RPI) * (D * 2);
+      load_to_lds_16(Kh, goff, dst);
+      load_to_lds_16(Vh, goff, dst + C::TILE_BYTES);
     }
   };
 
   // ---- this wave's 32 query rows go through LDS (second buffer) and are kept as B operands
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::KSTR;
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::QSTR;
   {
     u32x4 v[NP];
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) v[pass] = load_row_chunk_once<D>(Qh, src[pass], chunk16);
-    load_rows(0);
+    load_tile(0, 0);  // buffer 0 is not the Q staging area
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass)
-      *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::VPR) * C::KSTR + chunk16 * 8) = v[pass];
+      *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::CPR) * C::QSTR + chunk16 * 8) = v[pass];
   }
-  store_tile(0);  // buffer 0 is not the Q staging area
-  if (ntiles > 1) load_rows(1);
-  __syncthreads();
+  __syncthreads();  // Q rows staged (tile 0 is waited for at the top of the tile loop)
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk)
-    qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::KSTR + 16 * kk + 8 * g2);
+    qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::QSTR + 16 * kk + 8 * g2);
   if (p.rope_table) {
     // RoPE on the query's ORIGINAL position (App. A; Sec. 4.2), applied to the operand fragments: a lane
     // holds elements 16kk + 8*g2 .. +7 of its row for every kk, so both members of a pair are its own --
@@ -270,6 +256,26 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   const int Rl = circular ? R : min(R, max(n - 1 - s, 0));
   const unsigned LRl = (unsigned)(Ll + Rl);
 
+  // ---- per-lane element offsets of the operand reads inside a swizzled tile (without the block's rows)
+  // K operand kk: row c32 (+32 kb), logical chunk 2 kk + g2
+  int koff[D / 16];
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) koff[kk] = c32 * D + 8 * ((2 * kk + g2) ^ swz<D>(c32));
+  // V operand (db, half): the transposing read of lane (G = lane / 16, j = lane % 16) takes 8 bytes of row
+  // 4 (G / 2) + j / 4 (+8 for the second half) at columns 32 db + 16 (G % 2) + 4 (j % 4) ..+3
+  int voff[D / 32][2];
+  {
+    const int G = lane >> 4, j16 = lane & 15;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int row = 4 * (G >> 1) + (j16 >> 2) + 8 * hf;
+        const int col = 32 * db + 16 * (G & 1) + 4 * (j16 & 3);
+        voff[db][hf] = row * D + 8 * ((col >> 3) ^ swz<D>(row)) + (col & 7);
+      }
+  }
+
   const float cs = p.scale * kLog2e;  // exp(scale*x) = exp2(cs*x)
   const float lazy = 8.0f / cs;       // move the reference maximum only for jumps above 2^8
   float m_ref = -INFINITY, l_run = 0.f;
@@ -282,19 +288,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
   // one tile; BUF (0/1) is a compile-time constant so that all LDS addresses are immediates
   auto do_tile = [&](const int tile, auto bufc) {
     constexpr int buf = decltype(bufc)::value;
-    // tile's buffer is complete and visible; everyone is done with the other buffer (tile-1, Q staging)
+    // this wave's share of the tile has landed; after the barrier the whole tile is visible and everyone
+    // is done with the other buffer (tile-1, Q staging)
+    wait_all_loads();
     __syncthreads();
     if (tid < BN) {  // indices: tile+3 -> ring, tile+4 -> register
       ring[((tile + 3) & (C::RING - 1)) * BN + tid] = pk_reg;
       if (CAUSAL == CAUSAL_I16) ring16[((tile + 3) & (C::RING - 1)) * BN + pos16] = (short)(pk_reg - 32768);
       if (tile + 4 < ntiles) pk_reg = tile_row_orig(tile + 4);
     }
-    if (tile + 1 < ntiles) {
-      store_tile(buf ^ 1);
-      if (tile + 2 < ntiles) load_rows(tile + 2);
-    }
+    if (tile + 1 < ntiles) load_tile(tile + 1, buf ^ 1);
     const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES);
-    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES + C::KBYTES);
+    const bf16_t* Vs = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES + C::TILE_BYTES);
     const int* pk_lds = ring + (tile & (C::RING - 1)) * BN;
 
     const int t0 = t_lo + tile * BN;
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
         bf16x8 ka[D / 16];  // all K operands of the block are requested before the first product
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
-          ka[kk] = *reinterpret_cast<const bf16x8*>(Ks + (32 * kb + c32) * C::KSTR + 16 * kk + 8 * g2);
+          ka[kk] = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[kk]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) sacc[kb] = mfma_bf16(ka[kk], qf[kk], sacc[kb]);
@@ -423,7 +428,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
     }
 
     // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts tile rows 32kb+16c+{0..3,8..11}+4*g2 (+4 for the
-    // second half of the lane's 8 values); V^T rows keep exactly those 8 slots contiguous.
+    // second half of the lane's 8 values); the transposing read collects them from the row-major V tile.
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (!act[kb]) continue;
@@ -431,8 +436,10 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(Vt + (32 * db + c32) * C::VTSTR + 32 * kb + 16 * c + 8 * g2);
-          oacc[db] = mfma_bf16(a, pf[kb][c], oacc[db]);
+          const bf16_t* vb = Vs + (32 * kb + 16 * c) * D;
+          const s16x4 lo = lds_read_tr16(vb + voff[db][0]), hi = lds_read_tr16(vb + voff[db][1]);
+          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, a), pf[kb][c], oacc[db]);
         }
     }
   };
@@ -463,7 +470,7 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
       }
   }
 
-  bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::KSTR;
+  bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::QSTR;
   auto stage_and_store = [&](const f32x16* acc, void* dst_tensor) {
     __syncthreads();  // the staging area is free (last tile consumed / previous staging pass stored)
 #pragma unroll
@@ -473,18 +480,18 @@ __global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, cons
         u32x2 w;
         w[0] = pack_bf16(acc[db][4 * mq + 0], acc[db][4 * mq + 1]);
         w[1] = pack_bf16(acc[db][4 * mq + 2], acc[db][4 * mq + 3]);
-        *reinterpret_cast<u32x2*>(Os + c32 * C::KSTR + 32 * db + 8 * mq + 4 * g2) = w;
+        *reinterpret_cast<u32x2*>(Os + c32 * C::QSTR + 32 * db + 8 * mq + 4 * g2) = w;
       }
     wave_lds_sync();  // the staging rows are this wave's own
     int dst[NP];
 #pragma unroll
-    for (int pass = 0; pass < NP; ++pass) dst[pass] = rowstash[wave * 32 + pass * C::WRPP + lane / C::VPR];
+    for (int pass = 0; pass < NP; ++pass) dst[pass] = rowstash[wave * 32 + pass * C::WRPP + lane / C::CPR];
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) {
-      const int row = pass * C::WRPP + lane / C::VPR;
+      const int row = pass * C::WRPP + lane / C::CPR;
       if (s_w0 + row < n) {
         const size_t eoff = (head_row0 + dst[pass]) * D + chunk16 * 8;
-        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Os + row * C::KSTR + chunk16 * 8),
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Os + row * C::QSTR + chunk16 * 8),
                                     reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(dst_tensor) + eoff));
       }
     }
