@@ -92,7 +92,7 @@ enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 
 // PERM = false: identity permutation (plain windowed attention); no index loads are generated.
 template <int D, bool PERM, int CAUSAL>
-__global__ __launch_bounds__(NT, 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+__global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                               const int hshift) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
