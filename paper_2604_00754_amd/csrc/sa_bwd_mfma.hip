@@ -45,16 +45,20 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 template <int D, int BN_>
 struct Cfg {
   static constexpr int BN = BN_;         // streamed slots per tile
-  static constexpr int STR = D + 8;      // bf16 per LDS row (+16 B pad)
+  static constexpr int STR = D + 8;      // bf16 per row of the wave-private staging areas (+16 B pad)
   static constexpr int VPR = D / 8;      // 16-byte vectors per row
-  static constexpr int RPP = NT / VPR;
-  static constexpr int NV = BN / RPP;
+  static constexpr int RPP = NT / VPR;   // streamed rows the workgroup moves with one instruction per wave
+  static constexpr int NV = BN / RPP;    // such instructions per tile and operand
   static constexpr int WRPP = 64 / VPR;  // rows one wave moves per pass
   static constexpr int SP = 32 / WRPP;   // passes for a wave's 32 stationary rows
-  static constexpr int TILE_BYTES = BN * STR * 2;
-  static constexpr int STAGE_BYTES = 4 * 32 * STR * 2;  // 32 stationary rows of each of the 4 waves
-  static constexpr int AREA_BYTES = 2 * TILE_BYTES > 2 * STAGE_BYTES ? 2 * TILE_BYTES : 2 * STAGE_BYTES;
-  static constexpr int LDS_BYTES = AREA_BYTES + 3 * BN * 4;
+  static constexpr int TILE_BYTES = BN * D * 2;           // one streamed operand tile: rows unpadded, chunks swizzled
+  static constexpr int BUF_BYTES = 2 * TILE_BYTES;        // the two streamed operands of a tile
+  static constexpr int STAGE_BYTES = 4 * 32 * STR * 2;    // 32 staged rows of each of the 4 waves
+  // buffer 0 | buffer 1, which the staging area shares (it is used before tile 1 is requested and after
+  // the last tile) | per-slot values of two tiles
+  static constexpr int AREA_BYTES = BUF_BYTES + (BUF_BYTES > STAGE_BYTES ? BUF_BYTES : STAGE_BYTES);
+  static constexpr int SLOT_BYTES = 3 * BN * 4;
+  static constexpr int LDS_BYTES = AREA_BYTES + 2 * SLOT_BYTES;
   static_assert(BN <= NT && BN % 32 == 0 && NV >= 1, "one thread per streamed slot for the per-slot values");
 };
 
@@ -146,10 +150,6 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
   using C = Cfg<D, 64>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* Vs = reinterpret_cast<bf16_t*>(smem + C::TILE_BYTES);
-  int* pk_lds = reinterpret_cast<int*>(smem + C::AREA_BYTES);
-  short* pk16_lds = reinterpret_cast<short*>(smem + C::AREA_BYTES);  // CAUSAL_I16 keeps 16-bit positions instead
 
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
@@ -185,7 +185,12 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
   }
   const int ntiles = (t_hi - t_lo + BN) / BN;
 
-  const int ld_row = tid / C::VPR, ld_chunk = tid % C::VPR;
+  // streamed tiles: K | V rows of 64 key slots, fetched through the index tensor by direct global-to-LDS
+  // loads one tile ahead (double buffered, one barrier per tile).  Instruction v of a wave fills rows
+  // v*RPP + wave*WRPP .. of the tile; the lane delivers physical chunk lane % VPR of its row.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int ld_row = tid / C::VPR;
+  const uint32_t ld_chunk_off = (uint32_t)((((tid % C::VPR)) ^ swz<D>(ld_row)) * 16);
   const int pk_pos = acc_order_pos(tid & (BN - 1));
   int idx[C::NV];
   int pk_next = 0;
@@ -198,16 +203,21 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
     }
     if (CAUSAL != CAUSAL_NONE && tid < BN) pk_next = slot_to_orig(perm, wrap_slot(min(t0 + tid, t_hi), n));
   };
-  u32x4 kreg[C::NV], vreg[C::NV];
-  auto load_rows = [&]() {
+  // requests the tile whose indices load_idx fetched last, and publishes its causal positions
+  auto request_tile = [&](const int buf) {
 #pragma unroll
     for (int v = 0; v < C::NV; ++v) {
-      kreg[v] = *reinterpret_cast<const u32x4*>(Kh + (size_t)idx[v] * D + ld_chunk * 8);
-      vreg[v] = *reinterpret_cast<const u32x4*>(Vh + (size_t)idx[v] * D + ld_chunk * 8);
+      const uint32_t goff = (uint32_t)idx[v] * (uint32_t)(D * 2) + ld_chunk_off;
+      const uint32_t dst = lds0 + buf * C::BUF_BYTES + (v * C::RPP + wave * C::WRPP) * (D * 2);
+      load_to_lds_16(Kh, goff, dst);
+      load_to_lds_16(Vh, goff, dst + C::TILE_BYTES);
     }
+    if (CAUSAL == CAUSAL_I32 && tid < BN) reinterpret_cast<int*>(smem + C::AREA_BYTES + buf * C::SLOT_BYTES)[tid] = pk_next;
+    if (CAUSAL == CAUSAL_I16 && tid < BN)
+      reinterpret_cast<short*>(smem + C::AREA_BYTES + buf * C::SLOT_BYTES)[pk_pos] = (short)(pk_next - 32768);
   };
 
-  // prologue: every index, then every row (stationary Q and dO, first K/V tile), then the staging
+  // prologue: every index, then every row (first K/V tile, stationary Q and dO), then the staging
   int st_src[C::SP];
   stationary_src<C>(perm, s_w0, n, lane, st_src);
   const int orig_q = slot_to_orig(perm, min(s, n - 1));
@@ -217,19 +227,23 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
     u32x4 qrow[C::SP], grow[C::SP];
     stationary_rows<C, D>(Qh, st_src, lane, qrow);
     stationary_rows<C, D>(dOh, st_src, lane, grow);
-    load_rows();
-    bf16_t* stage_q = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::STR;
-    bf16_t* stage_g = reinterpret_cast<bf16_t*>(smem + C::STAGE_BYTES) + wave * 32 * C::STR;
-    stationary_put<C>(stage_q, lane, qrow);
-    stationary_put<C>(stage_g, lane, grow);
+    request_tile(0);
+    if (ntiles > 1) load_idx(1);
+    bf16_t* stage = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::STR;  // buffer 1 is still free
+    stationary_put<C>(stage, lane, qrow);
     wave_lds_sync();
-    stationary_get<C, D>(stage_q, lane, qf);
-    stationary_get<C, D>(stage_g, lane, gf);
+    stationary_get<C, D>(stage, lane, qf);
+    wave_lds_sync();
+    stationary_put<C>(stage, lane, grow);
+    wave_lds_sync();
+    stationary_get<C, D>(stage, lane, gf);
   }
   const float lse2 = p.lse_in[head_row0 + orig_q] * kLog2e;
   const float Dq = p.Dsum[head_row0 + orig_q];
-  int pk_cur = pk_next;
-  if (ntiles > 1) load_idx(1);
+
+  int koff[D / 16], troff[D / 32][2];
+  swizzled_row_offsets<D>(lane, koff);
+  swizzled_tr_offsets<D>(lane, troff);
 
   const int Ll = circular ? L : min(L, max(s, 0));
   const int Rl = circular ? R : min(R, max(n - 1 - s, 0));
@@ -244,21 +258,19 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
     for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
 
   for (int tile = 0; tile < ntiles; ++tile) {
-    __syncthreads();
-#pragma unroll
-    for (int v = 0; v < C::NV; ++v) {
-      const int row = v * C::RPP + ld_row;
-      *reinterpret_cast<u32x4*>(Ks + row * C::STR + ld_chunk * 8) = kreg[v];
-      *reinterpret_cast<u32x4*>(Vs + row * C::STR + ld_chunk * 8) = vreg[v];
-    }
-    if (CAUSAL == CAUSAL_I32 && tid < BN) pk_lds[tid] = pk_cur;
-    if (CAUSAL == CAUSAL_I16 && tid < BN) pk16_lds[pk_pos] = (short)(pk_cur - 32768);
+    const int buf = tile & 1;
+    // this wave's share of the tile has landed; after the barrier the whole tile is visible and everyone
+    // is done with the other buffer (the tile before, the staging of the prologue)
+    wait_all_loads();
     __syncthreads();
     if (tile + 1 < ntiles) {
-      load_rows();
-      pk_cur = pk_next;
+      request_tile(buf ^ 1);
       if (tile + 2 < ntiles) load_idx(tile + 2);
     }
+    const bf16_t* Ks = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES);
+    const bf16_t* Vs = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES + C::TILE_BYTES);
+    const int* pk_lds = reinterpret_cast<const int*>(smem + C::AREA_BYTES + buf * C::SLOT_BYTES);
+    const short* pk16_lds = reinterpret_cast<const short*>(smem + C::AREA_BYTES + buf * C::SLOT_BYTES);
     const int t0 = t_lo + tile * BN;
 #pragma unroll
     for (int kb = 0; kb < BN / 32; ++kb) {
@@ -272,9 +284,9 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
       for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Ks + (32 * kb + c32) * C::STR + 16 * kk + 8 * g2);
+        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[kk]);
         sacc = mfma_bf16(ka, qf[kk], sacc);    // S^T = K Q^T
-        const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vs + (32 * kb + c32) * C::STR + 16 * kk + 8 * g2);
+        const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vs + 32 * kb * D + koff[kk]);
         dpacc = mfma_bf16(va, gf[kk], dpacc);  // dP^T = V dO^T
       }
       if (CAUSAL == CAUSAL_I32) {
@@ -324,8 +336,8 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
       }
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {  // dQ^T += K^T dS^T
-        dqacc[db] = mfma_bf16(lds_read_transposed_a(Ks, C::STR, 32 * kb, 32 * db, lane), dsf0, dqacc[db]);
-        dqacc[db] = mfma_bf16(lds_read_transposed_a(Ks, C::STR, 32 * kb + 16, 32 * db, lane), dsf1, dqacc[db]);
+        dqacc[db] = mfma_bf16(lds_read_transposed_swz(Ks + (32 * kb) * D, troff[db]), dsf0, dqacc[db]);
+        dqacc[db] = mfma_bf16(lds_read_transposed_swz(Ks + (32 * kb + 16) * D, troff[db]), dsf1, dqacc[db]);
       }
     }
   }
@@ -341,12 +353,6 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
   using C = Cfg<D, D == 64 ? DKV_BN : 64>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* Gs = reinterpret_cast<bf16_t*>(smem + C::TILE_BYTES);
-  int* pq_lds = reinterpret_cast<int*>(smem + C::AREA_BYTES);
-  short* pq16_lds = reinterpret_cast<short*>(smem + C::AREA_BYTES);  // CAUSAL_I16 keeps 16-bit positions instead
-  float* lse_lds = reinterpret_cast<float*>(smem + C::AREA_BYTES + BN * 4);
-  float* dd_lds = reinterpret_cast<float*>(smem + C::AREA_BYTES + 2 * BN * 4);
 
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
@@ -394,6 +400,9 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
   int orig_k = 0;
   int st_src[C::SP];
   const int pq_pos = acc_order_pos(tid & (BN - 1));
+  int koff[D / 16], troff[D / 32][2];
+  swizzled_row_offsets<D>(lane, koff);
+  swizzled_tr_offsets<D>(lane, troff);
   for (int hg = hg_begin; hg < hg_end; ++hg) {
     const int hq = hk * p.g + hg;
     const int32_t* __restrict__ perm_h =
@@ -408,77 +417,104 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
     const float* __restrict__ lse_h = p.lse_in + head_row0;
     const float* __restrict__ dd_h = p.Dsum + head_row0;
 
-    const int ld_row = tid / C::VPR, ld_chunk = tid % C::VPR;
-    int idx[C::NV];
-    int pq_next = 0;
-    auto load_idx = [&](int tile) {
-      const int s0 = s_lo + tile * BN;
-#pragma unroll
-      for (int v = 0; v < C::NV; ++v) {
-        const int sq = min(s0 + v * C::RPP + ld_row, s_hi);
-        idx[v] = slot_to_orig(perm, wrap_slot(sq, n));
-      }
-      if (tid < BN) pq_next = slot_to_orig(perm, wrap_slot(min(s0 + tid, s_hi), n));
+    // streamed tiles: Q | dO rows of BN query slots, fetched through the index tensor by direct
+    // global-to-LDS loads one tile ahead (double buffered, one barrier per tile), with the per-slot
+    // values (causal position, LSE, -D) of the tile beside them.  Row indices are loaded one tile, the
+    // slot's own position two tiles, LSE and D one tile before the tile is requested.
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    const int ld_row = tid / C::VPR;
+    const uint32_t ld_chunk_off = (uint32_t)(((tid % C::VPR) ^ swz<D>(ld_row)) * 16);
+    auto row_index = [&](int tile, int v) -> int {
+      return slot_to_orig(perm, wrap_slot(min(s_lo + tile * BN + v * C::RPP + ld_row, s_hi), n));
     };
-    u32x4 qreg[C::NV], greg[C::NV];
-    float lse_reg = 0.f, dd_reg = 0.f;
-    int pq_cur = 0;
-    auto load_rows = [&]() {
+    auto slot_position = [&](int tile) -> int {  // tid < BN
+      return slot_to_orig(perm, wrap_slot(min(s_lo + tile * BN + tid, s_hi), n));
+    };
+    int idx[C::NV];
+    int pq_w = 0, pq_n = 0;
+    float lse_w = 0.f, dd_w = 0.f;
+    // requests the tile whose row indices are in idx and publishes the per-slot values held in *_w
+    auto request_tile = [&](const int buf) {
 #pragma unroll
       for (int v = 0; v < C::NV; ++v) {
-        qreg[v] = *reinterpret_cast<const u32x4*>(Qh + (size_t)idx[v] * D + ld_chunk * 8);
-        greg[v] = *reinterpret_cast<const u32x4*>(dOh + (size_t)idx[v] * D + ld_chunk * 8);
+        const uint32_t goff = (uint32_t)idx[v] * (uint32_t)(D * 2) + ld_chunk_off;
+        const uint32_t dst = lds0 + buf * C::BUF_BYTES + (v * C::RPP + wave * C::WRPP) * (D * 2);
+        load_to_lds_16(Qh, goff, dst);
+        load_to_lds_16(dOh, goff, dst + C::TILE_BYTES);
       }
       if (tid < BN) {
-        pq_cur = pq_next;
-        lse_reg = lse_h[pq_next] * kLog2e;
-        dd_reg = dd_h[pq_next];
+        char* slot = smem + C::AREA_BYTES + buf * C::SLOT_BYTES;
+        if (CAUSAL == CAUSAL_I32) reinterpret_cast<int*>(slot)[tid] = pq_w;
+        if (CAUSAL == CAUSAL_I16) reinterpret_cast<short*>(slot)[pq_pos] = (short)(pq_w - 32767);
+        reinterpret_cast<float*>(slot + BN * 4)[tid] = lse_w;
+        reinterpret_cast<float*>(slot + 2 * BN * 4)[tid] = -dd_w;  // dP starts from -D, so that the product leaves dP - D
       }
     };
+    auto load_slot_values = [&]() {  // LSE and D of the slot whose position is in pq_w
+      if (tid < BN) {
+        lse_w = lse_h[pq_w] * kLog2e;
+        dd_w = dd_h[pq_w];
+      }
+    };
+    if (hg != hg_begin) __syncthreads();  // a slower wave may still read the previous head's last tile
     // every index first, then every row (stationary K and V, first Q/dO tile), then the staging
     if (reload) {
       stationary_src<C>(perm, t_w0, n, lane, st_src);
       orig_k = slot_to_orig(perm, min(t, n - 1));
     }
-    load_idx(0);
+#pragma unroll
+    for (int v = 0; v < C::NV; ++v) idx[v] = row_index(0, v);
+    int pq_1 = 0;
+    if (tid < BN) {
+      pq_w = slot_position(0);
+      pq_1 = slot_position(1);
+      pq_n = slot_position(2);
+    }
+    load_slot_values();
     if (reload) {
       u32x4 krow[C::SP], vrow[C::SP];
       stationary_rows<C, D>(Kh, st_src, lane, krow);
       stationary_rows<C, D>(Vh, st_src, lane, vrow);
-      load_rows();
-      bf16_t* stage_v = reinterpret_cast<bf16_t*>(smem + C::STAGE_BYTES) + wave * 32 * C::STR;
-      if (hg != hg_begin) __syncthreads();  // a slower wave may still read the previous head's last tile
-      stationary_put<C>(stage, lane, krow);
-      stationary_put<C>(stage_v, lane, vrow);
+      request_tile(0);
+      bf16_t* stage_kv = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::STR;  // buffer 1 is still free
+      stationary_put<C>(stage_kv, lane, krow);
       wave_lds_sync();
-      stationary_get<C, D>(stage, lane, kf);
-      stationary_get<C, D>(stage_v, lane, vf);
+      stationary_get<C, D>(stage_kv, lane, kf);
+      wave_lds_sync();
+      stationary_put<C>(stage_kv, lane, vrow);
+      wave_lds_sync();
+      stationary_get<C, D>(stage_kv, lane, vf);
     } else {
-      load_rows();
+      request_tile(0);
     }
-    if (ntiles > 1) load_idx(1);
+    pq_w = pq_1;
+    load_slot_values();
+#pragma unroll
+    for (int v = 0; v < C::NV; ++v) idx[v] = row_index(1, v);
     // visible iff the query's original position >= the key's: (orig_k - 1) - pq < 0, on positions biased by 32767
     const s16x2 okm1 = {(short)(orig_k - 32768), (short)(orig_k - 32768)};
 
     for (int tile = 0; tile < ntiles; ++tile) {
-      __syncthreads();
-#pragma unroll
-      for (int v = 0; v < C::NV; ++v) {
-        const int row = v * C::RPP + ld_row;
-        *reinterpret_cast<u32x4*>(Qs + row * C::STR + ld_chunk * 8) = qreg[v];
-        *reinterpret_cast<u32x4*>(Gs + row * C::STR + ld_chunk * 8) = greg[v];
-      }
-      if (tid < BN) {
-        if (CAUSAL == CAUSAL_I32) pq_lds[tid] = pq_cur;
-        if (CAUSAL == CAUSAL_I16) pq16_lds[pq_pos] = (short)(pq_cur - 32767);
-        lse_lds[tid] = lse_reg;
-        dd_lds[tid] = -dd_reg;  // dP starts from -D, so that the product leaves dP - D
-      }
+      const int buf = tile & 1;
+      // this wave's share of the tile has landed; after the barrier the whole tile is visible and
+      // everyone is done with the other buffer (the tile before, the staging of the prologue)
+      wait_all_loads();
       __syncthreads();
       if (tile + 1 < ntiles) {
-        load_rows();
-        if (tile + 2 < ntiles) load_idx(tile + 2);
+        request_tile(buf ^ 1);
+        pq_w = pq_n;
+        load_slot_values();
+#pragma unroll
+        for (int v = 0; v < C::NV; ++v) idx[v] = row_index(tile + 2, v);
+        if (tid < BN) pq_n = slot_position(tile + 3);
       }
+      const bf16_t* Qs = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES);
+      const bf16_t* Gs = reinterpret_cast<const bf16_t*>(smem + buf * C::BUF_BYTES + C::TILE_BYTES);
+      const char* slot = smem + C::AREA_BYTES + buf * C::SLOT_BYTES;
+      const int* pq_lds = reinterpret_cast<const int*>(slot);
+      const short* pq16_lds = reinterpret_cast<const short*>(slot);
+      const float* lse_lds = reinterpret_cast<const float*>(slot + BN * 4);
+      const float* dd_lds = reinterpret_cast<const float*>(slot + 2 * BN * 4);
       const int s0 = s_lo + tile * BN;
 #pragma unroll
       for (int qb = 0; qb < BN / 32; ++qb) {
@@ -496,9 +532,9 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
         }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qs + (32 * qb + c32) * C::STR + 16 * kk + 8 * g2);
+          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qs + 32 * qb * D + koff[kk]);
           sacc = mfma_bf16(qa, kf[kk], sacc);    // S = Q K^T
-          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(Gs + (32 * qb + c32) * C::STR + 16 * kk + 8 * g2);
+          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(Gs + 32 * qb * D + koff[kk]);
           dpacc = mfma_bf16(ga, vf[kk], dpacc);  // dP = dO V^T
         }
         // accumulator i is query row 32*qb + 8*(i/4) + 4*g2 + i%4 of the tile, key column = lane
@@ -552,10 +588,10 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
           // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over the 32 query rows of the block)
-          dvacc[db] = mfma_bf16(lds_read_transposed_a(Gs, C::STR, 32 * qb, 32 * db, lane), pf0, dvacc[db]);
-          dvacc[db] = mfma_bf16(lds_read_transposed_a(Gs, C::STR, 32 * qb + 16, 32 * db, lane), pf1, dvacc[db]);
-          dkacc[db] = mfma_bf16(lds_read_transposed_a(Qs, C::STR, 32 * qb, 32 * db, lane), dsf0, dkacc[db]);
-          dkacc[db] = mfma_bf16(lds_read_transposed_a(Qs, C::STR, 32 * qb + 16, 32 * db, lane), dsf1, dkacc[db]);
+          dvacc[db] = mfma_bf16(lds_read_transposed_swz(Gs + (32 * qb) * D, troff[db]), pf0, dvacc[db]);
+          dvacc[db] = mfma_bf16(lds_read_transposed_swz(Gs + (32 * qb + 16) * D, troff[db]), pf1, dvacc[db]);
+          dkacc[db] = mfma_bf16(lds_read_transposed_swz(Qs + (32 * qb) * D, troff[db]), dsf0, dkacc[db]);
+          dkacc[db] = mfma_bf16(lds_read_transposed_swz(Qs + (32 * qb + 16) * D, troff[db]), dsf1, dkacc[db]);
         }
       }
     }

@@ -49,26 +49,6 @@ struct Cfg {
   static_assert(BUF_BYTES % 16 == 0 && QBYTES % 16 == 0, "everything stays 16-byte aligned");
 };
 
-// K and V tiles lie in LDS as they lie in memory (row after row, no padding: that is how the direct
-// global-to-LDS loads deliver them), with the 16-byte chunks of a row permuted by an XOR with swz(row)
-// so that the two read patterns are conflict-free: 16 rows x the same chunk (K operand, ds_read_b128)
-// and 4 rows x 4 consecutive chunks (V operand, transposing 8-byte reads).
-template <int D>
-__device__ __forceinline__ int swz(int row) {
-  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
-}
-
-// 16 bytes per lane from global memory (scalar base + 32-bit lane offset) straight into LDS at
-// lds_byte_addr + 16 * lane.  The address travels in M0 and must be wave-uniform.  The compiler does not
-// see this load: it is waited for with an explicit s_waitcnt vmcnt(0) before the barrier that publishes
-// the tile.
-__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_byte_offset, uint32_t lds_byte_addr) {
-  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_byte_addr);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(lane_byte_offset), "s"(base)
-               : "memory");
-}
-__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
-
 // 16-byte chunk `chunk` of row `row` of a [n, D] bf16 head: a 32-bit byte offset from the (wave-uniform)
 // head pointer, so the address needs one vector instruction (the host checks n * D * 2 < 2^31).
 template <int D>
@@ -257,24 +237,9 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(cons
   const unsigned LRl = (unsigned)(Ll + Rl);
 
   // ---- per-lane element offsets of the operand reads inside a swizzled tile (without the block's rows)
-  // K operand kk: row c32 (+32 kb), logical chunk 2 kk + g2
-  int koff[D / 16];
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) koff[kk] = c32 * D + 8 * ((2 * kk + g2) ^ swz<D>(c32));
-  // V operand (db, half): the transposing read of lane (G = lane / 16, j = lane % 16) takes 8 bytes of row
-  // 4 (G / 2) + j / 4 (+8 for the second half) at columns 32 db + 16 (G % 2) + 4 (j % 4) ..+3
-  int voff[D / 32][2];
-  {
-    const int G = lane >> 4, j16 = lane & 15;
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int row = 4 * (G >> 1) + (j16 >> 2) + 8 * hf;
-        const int col = 32 * db + 16 * (G & 1) + 4 * (j16 & 3);
-        voff[db][hf] = row * D + 8 * ((col >> 3) ^ swz<D>(row)) + (col & 7);
-      }
-  }
+  int koff[D / 16], voff[D / 32][2];
+  swizzled_row_offsets<D>(lane, koff);
+  swizzled_tr_offsets<D>(lane, voff);
 
   const float cs = p.scale * kLog2e;  // exp(scale*x) = exp2(cs*x)
   const float lazy = 8.0f / cs;       // move the reference maximum only for jumps above 2^8
@@ -436,10 +401,7 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(cons
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) {
-          const bf16_t* vb = Vs + (32 * kb + 16 * c) * D;
-          const s16x4 lo = lds_read_tr16(vb + voff[db][0]), hi = lds_read_tr16(vb + voff[db][1]);
-          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, a), pf[kb][c], oacc[db]);
+          oacc[db] = mfma_bf16(lds_read_transposed_swz(Vs + (32 * kb + 16 * c) * D, voff[db]), pf[kb][c], oacc[db]);
         }
     }
   };

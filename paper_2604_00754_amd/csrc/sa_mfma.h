@@ -34,6 +34,59 @@ __device__ __forceinline__ bf16x8 lds_read_transposed_a(const bf16_t* tile, int 
   return __builtin_bit_cast(bf16x8, a);
 }
 
+// K and V tiles lie in LDS as they lie in memory (row after row, no padding: that is how the direct
+// global-to-LDS loads deliver them), with the 16-byte chunks of a row permuted by an XOR with swz(row)
+// so that the two read patterns are conflict-free: 16 rows x the same chunk (K operand, ds_read_b128)
+// and 4 rows x 4 consecutive chunks (V operand, transposing 8-byte reads).
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+// 16 bytes per lane from global memory (scalar base + 32-bit lane offset) straight into LDS at
+// lds_byte_addr + 16 * lane.  The address travels in M0 and must be wave-uniform.  The compiler does not
+// see this load: it is waited for with an explicit s_waitcnt vmcnt(0) before the barrier that publishes
+// the tile.
+__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_byte_offset, uint32_t lds_byte_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_byte_addr);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(lane_byte_offset), "s"(base)
+               : "memory");
+}
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
+
+// Element offsets, inside a swizzled tile of D-element rows, of a lane's operand reads (the rows of the
+// 32-row block are added by the caller):
+//   row operand kk (plain 16-byte read): row c32 of the block, logical chunk 2 kk + g2;
+//   transposed operand (db, half): the transposing read of lane (G = lane / 16, j = lane % 16) takes 8
+//   bytes of row 4 (G / 2) + j / 4 (+8 for the second half) of a 16-row block at columns
+//   32 db + 16 (G % 2) + 4 (j % 4) .. +3.
+template <int D>
+__device__ __forceinline__ void swizzled_row_offsets(int lane, int* off) {
+  const int g2 = lane >> 5, c32 = lane & 31;
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) off[kk] = c32 * D + 8 * ((2 * kk + g2) ^ swz<D>(c32));
+}
+template <int D>
+__device__ __forceinline__ void swizzled_tr_offsets(int lane, int (*off)[2]) {
+  const int G = lane >> 4, j16 = lane & 15;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int row = 4 * (G >> 1) + (j16 >> 2) + 8 * hf;
+      const int col = 32 * db + 16 * (G & 1) + 4 * (j16 & 3);
+      off[db][hf] = row * D + 8 * ((col >> 3) ^ swz<D>(row)) + (col & 7);
+    }
+}
+// A operand X^T for 16 contraction rows starting at `rows16` (a multiple of 16 rows into a swizzled tile):
+// the contraction rows are {0..3, 8..11} + 4*g (first four values of the lane) and +4 more (second four),
+// which is where the accumulators of a preceding 32x32 product keep the values that serve as B operand.
+__device__ __forceinline__ bf16x8 lds_read_transposed_swz(const bf16_t* rows16, const int* off2) {
+  const s16x4 lo = lds_read_tr16(rows16 + off2[0]), hi = lds_read_tr16(rows16 + off2[1]);
+  const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, a);
+}
+
 // Pack accumulators 8c..8c+7 of a lane as a bf16 B operand.
 __device__ __forceinline__ bf16x8 pack_b_operand(const float* v8) {
   u32x4 w;
