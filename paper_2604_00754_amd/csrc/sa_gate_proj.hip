@@ -256,18 +256,24 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 }
 
 // dW[o][k] += sum over a chunk of tokens of dz[t][o] * y[t][k].  Workgroup = 128 x 128 of dW, 4 waves
-// as 2 x 2, token step 64; both tiles are stored transposed ([feature][token], +16 B padding) so that
-// the token index is the contiguous one for the matrix instructions.  Tokens past n contribute zeros.
+// as 2 x 2.  The contraction runs over tokens, which is the slow index of both operands in memory, so
+// both tiles are brought in as they lie ([token][128 features], by direct global-to-LDS loads, unpadded
+// rows with swizzled 16-byte chunks) and both operands are read with the transposing LDS read: a lane
+// gets the same 8 tokens of one feature column for the A operand (dz^T) and the B operand (y).
+// Steps of 32 tokens, four buffers, three steps in flight.  Tokens past the chunk's end are zeroed in
+// the dz tile after it has landed.
 constexpr int WCHUNK = 4096;  // tokens per workgroup
-constexpr int WSTEP = 64;
-constexpr int WSTR = WSTEP + 8;
-constexpr int WTILE_BYTES = 128 * WSTR * 2;
+constexpr int WSTEP = 32;
+constexpr int WSTAGES = 4;
+constexpr int WTILE_BYTES = WSTEP * 128 * 2;  // one operand, one step
+constexpr int WSTAGE_BYTES = 2 * WTILE_BYTES;
+constexpr int WLOADS_PER_STAGE = 4;           // instructions per thread: 2 rows of 16 tokens x 2 operands
 
 template <int D>
 __global__ __launch_bounds__(GNT, 2) void gate_dw_bf16_kernel(const bf16_t* __restrict__ dz, const bf16_t* __restrict__ Yx,
                                                                float* __restrict__ dW, const int B, const int H, const int n,
                                                                const int num_ft, const int chunks_per_b, const long total_work) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * 2 * WTILE_BYTES];
+  __shared__ __attribute__((aligned(16))) char smem[WSTAGES * WSTAGE_BYTES];
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
   const int kt = (int)(work % num_ft);  // input-feature tile (columns of dW)
@@ -285,33 +291,32 @@ __global__ __launch_bounds__(GNT, 2) void gate_dw_bf16_kernel(const bf16_t* __re
   const int t_begin = ch * WCHUNK, t_end = min(t_begin + WCHUNK, n);
   const int nsteps = (t_end - t_begin + WSTEP - 1) / WSTEP;
 
-  // loader unit: tokens 4u..4u+3 (u = tid % 16) x 16-byte feature chunk tid / 16 (16 chunks = 128 features)
-  const int lu = tid & 15, lc = tid >> 4;
-  auto feat_base = [&](const bf16_t* X, int f0) -> const bf16_t* {  // row 0 of feature chunk lc of tile f0
-    const int f = f0 + lc * 8;
-    return X + ((size_t)b * H + f / D) * n * (size_t)D + f % D;
+  // loader: one instruction of a wave fills 4 token rows (256 bytes each) of a tile; the lane delivers
+  // physical chunk lane % 16 of token row wave * 4 + lane / 16 (+16 for the second instruction), i.e.
+  // fetches the logical chunk (lane % 16) ^ swz(row): 8 features of one head
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int ld_row = wave * 4 + (lane >> 4);
+  const int ld_feat = 8 * ((lane & 15) ^ swz<128>(ld_row));
+  auto feature_offset = [&](int f) -> uint32_t {  // bytes from the batch's first element to (token 0, feature f)
+    return (uint32_t)(((size_t)(f / D) * n * D + f % D) * 2);
   };
-  const bf16_t* zbase = feat_base(dz, ot * 128);
-  const bf16_t* ybase = feat_base(Yx, kt * 128);
-  u32x4 zreg[4], yreg[4];
-  auto load_step = [&](int st) {
-    const int t0 = t_begin + st * WSTEP + 4 * lu;
+  const bf16_t* zb = dz + (size_t)b * H * n * D;
+  const bf16_t* yb = Yx + (size_t)b * H * n * D;
+  const uint32_t zfeat = feature_offset(ot * 128 + ld_feat), yfeat = feature_offset(kt * 128 + ld_feat);
+  auto request_step = [&](int st) {  // steps past the last one fetch its rows again and are never used
+    const int buf = st & (WSTAGES - 1);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int t = t0 + j;
-      const bool live = t < t_end;
-      const size_t row = (size_t)(live ? t : t_end - 1) * D;
-      zreg[j] = *reinterpret_cast<const u32x4*>(zbase + row);
-      yreg[j] = *reinterpret_cast<const u32x4*>(ybase + row);
-      if (!live) { zreg[j] = u32x4{0u, 0u, 0u, 0u}; yreg[j] = u32x4{0u, 0u, 0u, 0u}; }
+    for (int j = 0; j < 2; ++j) {
+      const int token = min(t_begin + st * WSTEP + 16 * j + ld_row, t_end - 1);
+      const uint32_t trow = (uint32_t)token * (uint32_t)(D * 2);
+      const uint32_t dst = lds0 + buf * WSTAGE_BYTES + (16 * j + wave * 4) * 256;
+      load_to_lds_16(zb, zfeat + trow, dst);
+      load_to_lds_16(yb, yfeat + trow, dst + WTILE_BYTES);
     }
   };
-  auto store_step = [&](int buf) {
-    bf16_t* Zt = reinterpret_cast<bf16_t*>(smem + buf * 2 * WTILE_BYTES);
-    bf16_t* Yt = reinterpret_cast<bf16_t*>(smem + buf * 2 * WTILE_BYTES + WTILE_BYTES);
-    store_transposed_4x8(Zt + (8 * lc) * WSTR + 4 * lu, WSTR, zreg);
-    store_transposed_4x8(Yt + (8 * lc) * WSTR + 4 * lu, WSTR, yreg);
-  };
+
+  int troff[4][2];
+  swizzled_tr_offsets<128>(lane, troff);
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -321,31 +326,41 @@ __global__ __launch_bounds__(GNT, 2) void gate_dw_bf16_kernel(const bf16_t* __re
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[oi][ki][i] = 0.f;
 
-  load_step(0);
-  store_step(0);
-  if (nsteps > 1) load_step(1);
+  request_step(0);
+  request_step(1);
+  request_step(2);
   for (int st = 0; st < nsteps; ++st) {
-    const int buf = st & 1;
+    const int buf = st & (WSTAGES - 1);
+    // all but the two youngest steps of this wave have landed; after the barrier step st is visible and
+    // everyone is done with the buffer of step st - 1, which step st + 3 may now overwrite
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * WLOADS_PER_STAGE));  // vmcnt(8)
     __syncthreads();
-    if (st + 1 < nsteps) {
-      store_step(buf ^ 1);
-      if (st + 2 < nsteps) load_step(st + 2);
+    request_step(st + 3);
+    bf16_t* Zt = reinterpret_cast<bf16_t*>(smem + buf * WSTAGE_BYTES);
+    const bf16_t* Yt = reinterpret_cast<const bf16_t*>(smem + buf * WSTAGE_BYTES + WTILE_BYTES);
+    if (t_begin + (st + 1) * WSTEP > t_end) {  // ragged last step: tokens past the end contribute zeros
+      const int row = tid >> 3;
+      if (t_begin + st * WSTEP + row >= t_end) {
+        u32x4* r = reinterpret_cast<u32x4*>(Zt + row * 128 + (tid & 7) * 16);
+        r[0] = u32x4{0u, 0u, 0u, 0u};
+        r[1] = u32x4{0u, 0u, 0u, 0u};
+      }
+      __syncthreads();
     }
-    const bf16_t* Zt = reinterpret_cast<const bf16_t*>(smem + buf * 2 * WTILE_BYTES) + (64 * wo + c32) * WSTR + 8 * g2;
-    const bf16_t* Yt = reinterpret_cast<const bf16_t*>(smem + buf * 2 * WTILE_BYTES + WTILE_BYTES) + (64 * wk + c32) * WSTR + 8 * g2;
 #pragma unroll
     for (int ks = 0; ks < WSTEP / 16; ++ks) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
-      for (int oi = 0; oi < 2; ++oi) fa[oi] = *reinterpret_cast<const bf16x8*>(Zt + 32 * oi * WSTR + 16 * ks);
+      for (int oi = 0; oi < 2; ++oi) fa[oi] = lds_read_transposed_swz(Zt + 16 * ks * 128, troff[2 * wo + oi]);
 #pragma unroll
-      for (int ki = 0; ki < 2; ++ki) fb[ki] = *reinterpret_cast<const bf16x8*>(Yt + 32 * ki * WSTR + 16 * ks);
+      for (int ki = 0; ki < 2; ++ki) fb[ki] = lds_read_transposed_swz(Yt + 16 * ks * 128, troff[2 * wk + ki]);
 #pragma unroll
       for (int oi = 0; oi < 2; ++oi)
 #pragma unroll
         for (int ki = 0; ki < 2; ++ki) acc[oi][ki] = mfma_bf16(fa[oi], fb[ki], acc[oi][ki]);
     }
   }
+  wait_all_loads();  // the surplus steps requested near the end
   // accumulator 4q + x of lane (g2, c32): row o = 64wo + 32oi + 8q + 4g2 + x, column k = 64wk + 32ki + c32
 #pragma unroll
   for (int oi = 0; oi < 2; ++oi)
@@ -458,6 +473,7 @@ hipError_t launch_gate_proj_bwd_bf16(int B, int Hq, int n, int d, const void* Y_
   if (!(d == 64 || d == 128)) return hipErrorNotSupported;
   const long dm = (long)Hq * d;
   if (dm % 128 != 0) return hipErrorNotSupported;
+  if ((size_t)dm * n * 2 >= ((size_t)1 << 32)) return hipErrorNotSupported;  // 32-bit byte offsets inside a batch
   char* base = reinterpret_cast<char*>(ws);
   hipError_t e = gate_proj_bwd_branch(B, Hq, n, d, Y_sa, W_sa, G_sa, dY, dY_sa, dW_sa, base, st);
   if (e != hipSuccess || !dual) return e;
