@@ -294,7 +294,7 @@ def main():
     e = 2
     alg_bytes = wl.B * wl.n * (wl.Hq * 2 * wl.d * e + wl.Hkv * 2 * wl.d * e + wl.Hq * 4) + wl.n * 4
     tflops = band_flop / (launch_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128, true, 2>", "achieved": tflops,
+    roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128, true, 2, false>", "achieved": tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
                 "median_launch_ms": float(np.median(launch_samples)), "min_launch_ms": float(np.min(launch_samples)),

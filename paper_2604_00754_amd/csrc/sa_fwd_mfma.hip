@@ -71,8 +71,11 @@ __device__ __forceinline__ u32x4 load_row_chunk_once(const bf16_t* head, int row
 enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 
 // PERM = false: identity permutation (plain windowed attention); no index loads are generated.
-template <int D, bool PERM, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+// GATED = true: the variants of the gated forward (an unrounded fp32 copy of the result, or the gated sum of
+// Eq. 5 in the epilogue); they need more registers after the tile loop, so at d = 64 they run three
+// workgroups per CU where the plain kernel runs four.
+template <int D, bool PERM, int CAUSAL, bool GATED>
+__global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                               const int hshift) {
   using C = Cfg<D>;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
@@ -422,7 +425,7 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(cons
     for (int i = 0; i < 16; ++i) oacc[db][i] *= inv_l;
 
   // accumulator (db, 4mq..4mq+3) of a lane = elements 32db + 8mq + 4g2 .. +3 of its row
-  if (p.Y_f32_out && s < n) {  // first branch of the gated forward: keep an unrounded copy
+  if (GATED && p.Y_f32_out && s < n) {  // first branch of the gated forward: keep an unrounded copy
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -460,7 +463,7 @@ __global__ __launch_bounds__(NT, D == 64 ? 4 : 2) void fwd_mfma_bf16_kernel(cons
   };
 
   if (p.Y) stage_and_store(oacc, p.Y);
-  if (p.gate_mode) {
+  if (GATED && p.gate_mode) {
     // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other, formed in fp32 and rounded once
     const size_t r = s < n ? my_row : head_row0;
     float ga = 0.f, gb = 0.f;
@@ -502,8 +505,12 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
   // later key, the causal test would only repeat it
   const bool window_is_causal = !p.perm && !p.win.circular && p.win.R == 0;
   const int mode = (!p.causal || window_is_causal) ? CAUSAL_NONE : (p.n <= 65535 ? CAUSAL_I16 : CAUSAL_I32);
-#define SA_LAUNCH_FWD(PERM_, MODE_) \
-  hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_>), grid, block, 0, st, p, num_qt, total, hshift)
+#define SA_LAUNCH_FWD(PERM_, MODE_)                                                                              \
+  do {                                                                                                            \
+    if (gated) hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_, true>), grid, block, 0, st, p, num_qt, total, hshift); \
+    else hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_, false>), grid, block, 0, st, p, num_qt, total, hshift);      \
+  } while (0)
+  const bool gated = p.gate_mode != 0 || p.Y_f32_out != nullptr;
   if (p.perm) {
     if (mode == CAUSAL_NONE) SA_LAUNCH_FWD(true, CAUSAL_NONE);
     else if (mode == CAUSAL_I16) SA_LAUNCH_FWD(true, CAUSAL_I16);
