@@ -70,7 +70,7 @@ def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
             s_w0 = p0 + 32 * wave
             if s_w0 >= n:
                 continue  # such a wave still runs, on clamped rows; not counted
-            for blk in range(2 * ntiles):
+            for blk in range((BN // 32) * ntiles):
                 tb0 = t_lo + 32 * blk
                 dmax, dmin = tb0 + 31 - s_w0, tb0 - (s_w0 + 31)
                 if not (dmax < -L or dmin > R) and tb0 <= t_hi:
@@ -298,7 +298,8 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
                 "median_launch_ms": float(np.median(launch_samples)), "min_launch_ms": float(np.min(launch_samples)),
-                "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq, BM=128 // heads_per_workgroup(wl)),
+                "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq, BM=128 // heads_per_workgroup(wl),
+                                               BN=32 if wl.d == 128 else 64),
                 "caches": "not flushed between launches (see other_ops.cold_cache_ms)"}
     gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
     roofline_hbm = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",

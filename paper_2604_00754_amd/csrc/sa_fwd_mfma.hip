@@ -28,12 +28,22 @@
 namespace sa {
 namespace {
 
+#ifndef FWD_BN128
+#define FWD_BN128 32
+#endif
+#ifndef FWD_KG128
+#define FWD_KG128 4
+#endif
+#ifndef FWD_WGS128
+#define FWD_WGS128 3
+#endif
 constexpr int BM = 128;  // query rows per workgroup (slots x heads)
-constexpr int BN = 64;   // key slots per tile
 constexpr int NT = 256;  // threads per workgroup
 
 template <int D>
 struct Cfg {
+  static constexpr int BN = D == 128 ? FWD_BN128 : 64;  // key slots per tile
+  static constexpr int NB = BN / 32;     // 32-slot blocks per tile
   static constexpr int QSTR = D + 8;     // bf16 per row of the Q / O staging area: +16 B keeps 16 consecutive rows on distinct banks for 16-byte reads
   static constexpr int CPR = D / 8;      // 16-byte chunks per K/V row
   static constexpr int RPI = 64 / CPR;   // K/V rows one wave moves with one 16-byte-per-lane instruction
@@ -75,9 +85,10 @@ enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 // Eq. 5 in the epilogue); they need more registers after the tile loop, so at d = 64 they run three
 // workgroups per CU where the plain kernel runs four.
 template <int D, bool PERM, int CAUSAL, bool GATED>
-__global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+__global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : (GATED ? 2 : FWD_WGS128)) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                               const int hshift) {
   using C = Cfg<D>;
+  constexpr int BN = C::BN, NB = C::NB;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
 
   // 1 << hshift = query heads per workgroup (1, 2 or 4; a divisor of the group size).  Work list order: the
@@ -271,30 +282,38 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
     const int* pk_lds = ring + (tile & (C::RING - 1)) * BN;
 
     const int t0 = t_lo + tile * BN;
-    bool act[2], inside[2];
+    bool act[NB], inside[NB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NB; ++kb) {
       const int tb0 = t0 + 32 * kb;
       const int dmax = tb0 + 31 - s_w0, dmin = tb0 - (s_w0 + 31);
       act[kb] = !(dmax < -L || dmin > R) && tb0 <= t_hi;
       inside[kb] = dmin >= -L && dmax <= R && tb0 + 31 <= t_hi && s_w0 + 31 <= q_last;
     }
-    if (!act[0] && !act[1]) return;
+    bool any_act = false;
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb) any_act = any_act || act[kb];
+    if (!any_act) return;
 
     // ---- S^T = K Q^T for the active 32-slot blocks
-    f32x16 sacc[2];
+    f32x16 sacc[NB];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NB; ++kb) {
       if (act[kb]) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-        bf16x8 ka[D / 16];  // all K operands of the block are requested before the first product
+        // the K operands of the block are requested KG at a time, each group before its first product
+        constexpr int KG = D == 128 ? FWD_KG128 : D / 16;
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-          ka[kk] = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[kk]);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int k0 = 0; k0 < D / 16; k0 += KG) {
+          bf16x8 ka[KG];
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) sacc[kb] = mfma_bf16(ka[kk], qf[kk], sacc[kb]);
+          for (int kk = 0; kk < KG; ++kk) ka[kk] = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[k0 + kk]);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int kk = 0; kk < KG; ++kk) sacc[kb] = mfma_bf16(ka[kk], qf[k0 + kk], sacc[kb]);
+          if (k0 + KG < D / 16) __builtin_amdgcn_sched_barrier(0);
+        }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[kb][i] = -INFINITY;
@@ -313,7 +332,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
     };
     // ---- mask.  Accumulator i of block kb is key row 32*kb + 8*(i/4) + 4*g2 + i%4 of the tile.
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NB; ++kb) {
       if (!act[kb]) continue;
       if (CAUSAL == CAUSAL_I32) causal_to_neg_inf(sacc[kb], kb);
       if (!inside[kb]) {
@@ -330,7 +349,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
     // p = exp2(cs*(s - m_ref)) stays <= 2^8, and O and l carry the same reference, so O/l is unchanged
     float mx = sacc[0][0];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < NB; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
     mx = max_with_other_half(mx);
@@ -340,7 +359,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
         // are): take the maximum over the visible keys only before moving the reference
         float mv = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < NB; ++kb) {
           if (!act[kb]) continue;
           f32x16 t = sacc[kb];
           causal_to_neg_inf(t, kb);
@@ -359,9 +378,9 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
         for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     }
     const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * cs;
-    bf16x8 pf[2][2];
+    bf16x8 pf[NB][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NB; ++kb) {
       if (!act[kb]) continue;
       if (CAUSAL == CAUSAL_I16) {
         // pair e of the lane = accumulators 2e, 2e+1; the ring keeps their biased indices as one dword
@@ -398,7 +417,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : 2) void fwd_mfma_bf
     // ---- O^T += V^T P^T.  MFMA step (kb,c) contracts tile rows 32kb+16c+{0..3,8..11}+4*g2 (+4 for the
     // second half of the lane's 8 values); the transposing read collects them from the row-major V tile.
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < NB; ++kb) {
       if (!act[kb]) continue;
 #pragma unroll
       for (int c = 0; c < 2; ++c)
