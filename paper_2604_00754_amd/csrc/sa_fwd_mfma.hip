@@ -28,6 +28,12 @@
 namespace sa {
 namespace {
 
+#ifndef FWD_BN64
+#define FWD_BN64 64
+#endif
+#ifndef FWD_WGS64
+#define FWD_WGS64 4
+#endif
 #ifndef FWD_BN128
 #define FWD_BN128 32
 #endif
@@ -42,7 +48,7 @@ constexpr int NT = 256;  // threads per workgroup
 
 template <int D>
 struct Cfg {
-  static constexpr int BN = D == 128 ? FWD_BN128 : 64;  // key slots per tile
+  static constexpr int BN = D == 128 ? FWD_BN128 : FWD_BN64;  // key slots per tile
   static constexpr int NB = BN / 32;     // 32-slot blocks per tile
   static constexpr int QSTR = D + 8;     // bf16 per row of the Q / O staging area: +16 B keeps 16 consecutive rows on distinct banks for 16-byte reads
   static constexpr int CPR = D / 8;      // 16-byte chunks per K/V row
@@ -85,7 +91,7 @@ enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 // Eq. 5 in the epilogue); they need more registers after the tile loop, so at d = 64 they run three
 // workgroups per CU where the plain kernel runs four.
 template <int D, bool PERM, int CAUSAL, bool GATED>
-__global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : 4) : (GATED ? 2 : FWD_WGS128)) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+__global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 : FWD_WGS128)) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                               const int hshift) {
   using C = Cfg<D>;
   constexpr int BN = C::BN, NB = C::NB;
