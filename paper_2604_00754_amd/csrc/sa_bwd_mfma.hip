@@ -146,22 +146,29 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
 
 // ------------------------------------------------------------------------------------------ dQ
 template <int D, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work) {
+__global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+                                                                                            const int hshift) {
   using C = Cfg<D, 64>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
 
+  // 1 << hshift query heads of a KV group share the workgroup (as in the forward: the same 32 slots of
+  // up to four heads that read K/V through one permutation, one head per wave); 0: four 32-slot blocks of
+  // one head.  Work list order: the head sets of a KV group, then the next query tile.
   const long work = xcd_work_index(total_work);
   if (work < 0) return;
-  const int hg = (int)(work % p.g);
-  long rest = work / p.g;
+  const int sets = p.g >> hshift;
+  const int hset = (int)(work % sets);
+  long rest = work / sets;
   const int qt = (int)(rest % num_qt);
   rest /= num_qt;
   const int hk = (int)(rest % p.Hkv);
   const int b = (int)(rest / p.Hkv);
-  const int hq = hk * p.g + hg;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hq = hk * p.g + (hset << hshift) + (wave & ((1 << hshift) - 1));  // this wave's query head
+  const int bm = BM >> hshift;                                               // query slots of the workgroup
   const int g2 = lane >> 5, c32 = lane & 31;
   const int n = p.n, L = p.win.L, R = p.win.R;
   const bool circular = p.win.circular != 0;
@@ -173,9 +180,9 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
   const bf16_t* __restrict__ Kh = reinterpret_cast<const bf16_t*>(p.K) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   const bf16_t* __restrict__ Vh = reinterpret_cast<const bf16_t*>(p.V) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
 
-  const int p0 = qt * BM;
-  const int q_last = min(p0 + BM - 1, n - 1);
-  const int s_w0 = p0 + 32 * wave;
+  const int p0 = qt * bm;
+  const int q_last = min(p0 + bm - 1, n - 1);
+  const int s_w0 = p0 + 32 * (wave >> hshift);
   const int s = s_w0 + c32;
 
   int t_lo = p0 - L, t_hi = q_last + R;
@@ -612,15 +619,19 @@ inline int causal_mode(const Pass& p) {
 
 template <int D>
 hipError_t launch_dq_t(const Pass& p, hipStream_t st) {
-  const int num_qt = (p.n + BM - 1) / BM;
-  const long total = (long)num_qt * p.Hq * p.B;
+  // Query heads of a KV group that read K/V through the same permutation (or none) share a workgroup
+  const bool shared_perm = !p.perm || p.perm_H == 1;
+  const int hshift = !shared_perm ? 0 : (p.g % 4 == 0 ? 2 : (p.g % 2 == 0 ? 1 : 0));
+  const int bm = BM >> hshift;
+  const int num_qt = (p.n + bm - 1) / bm;
+  const long total = (long)num_qt * (p.Hq >> hshift) * p.B;
   const long blocks = xcd_grid_blocks(total);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks), block(NT);
   switch (causal_mode(p)) {
-    case CAUSAL_NONE: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_NONE>), grid, block, 0, st, p, num_qt, total); break;
-    case CAUSAL_I16: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I16>), grid, block, 0, st, p, num_qt, total); break;
-    default: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I32>), grid, block, 0, st, p, num_qt, total); break;
+    case CAUSAL_NONE: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_NONE>), grid, block, 0, st, p, num_qt, total, hshift); break;
+    case CAUSAL_I16: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I16>), grid, block, 0, st, p, num_qt, total, hshift); break;
+    default: hipLaunchKernelGGL((bwd_dq_mfma_bf16_kernel<D, CAUSAL_I32>), grid, block, 0, st, p, num_qt, total, hshift); break;
   }
   return hipGetLastError();
 }

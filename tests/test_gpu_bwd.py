@@ -111,6 +111,16 @@ def test_bwd_bf16_ragged_and_degenerate(n, w):
     run_bwd(1, 2, 1, n, 128, w, CIRC, 0, "bf16", seed=21)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 2), (6, 2), (3, 1), (16, 2)])
+def test_bwd_bf16_query_heads_of_a_group_share_a_workgroup(Hq, Hkv):
+    """One permutation for all heads (or none): the dQ kernel processes the query heads of a KV group 4, 2 or 1
+    at a time over the same slots, by group size (4, 2, 3, 3 and 8 here).  Ragged n, several window kinds."""
+    run_bwd(1, Hq, Hkv, 555, 128, 128, CIRC, 1, "bf16", seed=80 + Hq)
+    run_bwd(2, Hq, Hkv, 300, 64, 70, LIN, 0, "bf16", perm_B=2, seed=81 + Hq)
+    run_bwd(1, Hq, Hkv, 421, 64, 64, ONE, 1, "bf16", identity=True, seed=82 + Hq)
+    run_bwd(1, Hq, Hkv, 31, 64, 8, CIRC, 1, "bf16", seed=83 + Hq)
+
+
 def test_bwd_bf16_per_head_perm_with_grouped_heads():
     run_bwd(2, 8, 2, 600, 64, 128, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=30)
     run_bwd(1, 4, 4, 600, 64, 128, CIRC, 1, "bf16", perm_H=4, seed=31)
