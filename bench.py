@@ -52,6 +52,14 @@ def time_op(fn, steps, warmup):
     return wall, float(np.mean(samples))
 
 
+def time_side(fn, steps, warmup):
+    """Side measurements: the median of the per-call HIP-event times (a single slow call -- a clock ramp, a first
+    touch of a workspace -- would otherwise dominate the mean of a handful of calls).  Same return shape as
+    time_op."""
+    wall, _ = time_op(fn, steps, warmup)
+    return wall, float(np.median(time_op.last_samples_ms))
+
+
 def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
     """Flop of the matrix instructions the forward kernel issues at this shape (symmetric circular
     window): per wave (32 query slots) every 32-key block of the workgroup's tiles that any of its
@@ -125,12 +133,12 @@ def training_ops(sa, synth, dev, reps):
     Lswa, dga, dgl = torch.empty_like(Lsa), torch.empty_like(ga), torch.empty_like(gl)
     wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=dev, dtype=torch.uint8)
     wsb = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=dev, dtype=torch.uint8)
-    _, t_fwd = time_op(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Ysa, Lsa), reps, 2)
-    _, t_bwd = time_op(lambda: sa.sa_bwd(dsa, None, Q, K, V, perm, None, None, Ysa, None, Lsa, None, dY,
+    _, t_fwd = time_side(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Ysa, Lsa), reps, 2)
+    _, t_bwd = time_side(lambda: sa.sa_bwd(dsa, None, Q, K, V, perm, None, None, Ysa, None, Lsa, None, dY,
                                          dQ, dK, dV, None, None, wsb), reps, 2)
-    _, t_gfwd = time_op(lambda: sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa,
+    _, t_gfwd = time_side(lambda: sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa,
                                                     wsf), reps, 2)
-    _, t_gbwd = time_op(lambda: sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY,
+    _, t_gbwd = time_side(lambda: sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY,
                                           dQ, dK, dV, dga, dgl, wsb), reps, 2)
     # the gate projections of the paper's layer (Eq. 6 + Eq. 5) on the two branch outputs, d_model = H*d
     dm = H * d
@@ -138,14 +146,14 @@ def training_ops(sa, synth, dev, reps):
     Gsa, Gswa, dYsa, dYswa = (torch.empty_like(Q) for _ in range(4))
     dWsa, dWswa = torch.empty_like(Wsa), torch.empty_like(Wswa)
     wsg = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATE_PROJ_BWD), device=dev, dtype=torch.uint8)
-    _, t_gp = time_op(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
-    _, t_gpb = time_op(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
+    _, t_gp = time_side(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
+    _, t_gpb = time_side(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
                                                    dWsa, dWswa, wsg), reps, 2)
     # the whole layer of Alg. 2 in one call each way (both branches + gate projections)
     wsd = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_DUAL_PATH_BWD), device=dev, dtype=torch.uint8)
-    _, t_dpf = time_op(lambda: sa.sa_dual_path_fwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Y, Ysa, Yswa, Gsa, Gswa,
+    _, t_dpf = time_side(lambda: sa.sa_dual_path_fwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Y, Ysa, Yswa, Gsa, Gswa,
                                                    Lsa, Lswa), reps, 2)
-    _, t_dpb = time_op(lambda: sa.sa_dual_path_bwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Ysa, Yswa, Gsa, Gswa,
+    _, t_dpb = time_side(lambda: sa.sa_dual_path_bwd(dsa, dswa, Q, K, V, perm, Wsa, Wswa, Ysa, Yswa, Gsa, Gswa,
                                                    Lsa, Lswa, dY, dQ, dK, dV, dWsa, dWswa, wsd), reps, 2)
     del Gsa, Gswa, dYsa, dYswa, wsg, wsd
     flop_gp = 2 * 2.0 * B * n * dm * dm
@@ -177,8 +185,8 @@ def long_prefill_ops(sa, synth, dev, reps):
     Y = torch.empty_like(Q)
     dsa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
     dswa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
-    _, t_sa = time_op(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Y, None), reps, 1)
-    _, t_swa = time_op(lambda: sa.swa_fwd(dswa, Q, K, V, Y, None), reps, 1)
+    _, t_sa = time_side(lambda: sa.sa_fwd(dsa, Q, K, V, perm, Y, None), reps, 1)
+    _, t_swa = time_side(lambda: sa.swa_fwd(dswa, Q, K, V, Y, None), reps, 1)
     flop_sa = 4.0 * wl.n * band_slots(wl.n, wl.w, 0) * wl.d * wl.B * wl.Hq
     return {"long_prefill_128k": {
         "shape": "B1 Hq32 Hkv4 n131072 d128 w1024 bf16",
@@ -218,10 +226,10 @@ def table3_sweep(sa, synth, dev):
             sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY, dQ, dK, dV, dga, dgl, wsb)
 
         reps = 10 if n <= 8192 else 5
-        _, t_sa = time_op(lambda: fwd_bwd(dsa, perm), reps, 2)
-        _, t_swa = time_op(lambda: fwd_bwd(dswa, None), reps, 2)
-        _, t_g = time_op(gated, reps, 2)
-        _, t_full = time_op(lambda: fwd_bwd(dfull, None), 2 if n >= 16384 else 4, 1)
+        _, t_sa = time_side(lambda: fwd_bwd(dsa, perm), reps, 2)
+        _, t_swa = time_side(lambda: fwd_bwd(dswa, None), reps, 2)
+        _, t_g = time_side(gated, reps, 2)
+        _, t_full = time_side(lambda: fwd_bwd(dfull, None), 2 if n >= 16384 else 4, 1)
         out.append({"n": n, "sa_fwdbwd_ms": t_sa, "swa_fwdbwd_ms": t_swa, "gated_sa_swa_fwdbwd_ms": t_g,
                     "full_causal_fwdbwd_ms": t_full, "full_over_sa": t_full / t_sa, "gated_over_sa": t_g / t_sa})
         print(f"table3 n={n}: SA {t_sa:.3f} ms  SWA {t_swa:.3f}  gated {t_g:.3f}  full {t_full:.2f}  "
@@ -311,17 +319,17 @@ def main():
         swa_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16,
                                 0.0, 1, 1)
         Y2 = torch.empty_like(Q)
-        _, swa_ms = time_op(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
+        _, swa_ms = time_side(lambda: sa.swa_fwd(swa_desc, Q, K, V, Y2, None), max(10, args.steps // 4), 5)
         other = {"swa_fwd_ms": swa_ms, "swa_fwd_tokens_per_s": wl.B * wl.n / (swa_ms * 1e-3)}
         # gather + scatter with (almost) no attention work: w = 1, every token sees itself only
         w1_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, 1, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16,
                                0.0, 1, 1)
-        _, w1_ms = time_op(lambda: sa.sa_fwd(w1_desc, Q, K, V, perm, Y2, None), max(10, args.steps // 4), 5)
+        _, w1_ms = time_side(lambda: sa.sa_fwd(w1_desc, Q, K, V, perm, Y2, None), max(10, args.steps // 4), 5)
         other.update({"gather_scatter_w1_ms": w1_ms,
                       "gather_scatter_w1_GBps": alg_bytes / (w1_ms * 1e-3) / 1e9,
                       "gather_scatter_w1_frac_hbm": alg_bytes / (w1_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
         # the ceiling for that: gather + scatter alone (sa_permuted_copy), same rows, same index tensor
-        _, pc_ms = time_op(lambda: sa.sa_permuted_copy(desc, Q, K, V, perm, Y2), max(10, args.steps // 4), 5)
+        _, pc_ms = time_side(lambda: sa.sa_permuted_copy(desc, Q, K, V, perm, Y2), max(10, args.steps // 4), 5)
         pc_bytes = alg_bytes - wl.B * wl.Hq * wl.n * 4  # no LSE
         other.update({"permuted_copy_ms": pc_ms, "permuted_copy_GBps": pc_bytes / (pc_ms * 1e-3) / 1e9,
                       "permuted_copy_frac_hbm": pc_bytes / (pc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
@@ -329,7 +337,7 @@ def main():
         # stream with no index tensor reaches on this GPU
         flat_src = torch.empty(pc_bytes // 2, device=dev, dtype=torch.uint8)
         flat_dst = torch.empty_like(flat_src)
-        _, cp_ms = time_op(lambda: flat_dst.copy_(flat_src), max(10, args.steps // 4), 5)
+        _, cp_ms = time_side(lambda: flat_dst.copy_(flat_src), max(10, args.steps // 4), 5)
         other.update({"plain_copy_ms": cp_ms, "plain_copy_GBps": pc_bytes / (cp_ms * 1e-3) / 1e9})
         del flat_src, flat_dst
         # the headline launch with cold caches: a 1 GiB device copy between launches evicts L2 and MALL
@@ -349,23 +357,23 @@ def main():
             del cs, cd
         # on-device permutation sampling (one layer, one permutation shared by the heads)
         sampled = torch.empty((1, 1, wl.n), device=dev, dtype=torch.int32)
-        _, sp_ms = time_op(lambda: sa.sa_sample_perm(desc, 1, 0, sampled), 10, 2)
+        _, sp_ms = time_side(lambda: sa.sa_sample_perm(desc, 1, 0, sampled), 10, 2)
         d8k = sa.make_desc(4, 16, 16, 8192, 64, 256)
         sampled8k = torch.empty((1, 1, 8192), device=dev, dtype=torch.int32)
-        _, sp8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k), 10, 2)
+        _, sp8_ms = time_side(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k), 10, 2)
         other.update({"sample_perm_n32768_ms": sp_ms, "sample_perm_n8192_ms": sp8_ms})
         # the same permutations through the bucketed O(n) path (needs a workspace)
         wss = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_SAMPLE_PERM), device=dev, dtype=torch.uint8)
-        _, spw_ms = time_op(lambda: sa.sa_sample_perm(desc, 1, 0, sampled, wss), 10, 2)
+        _, spw_ms = time_side(lambda: sa.sa_sample_perm(desc, 1, 0, sampled, wss), 10, 2)
         wss8 = torch.empty(sa.sa_workspace_bytes(d8k, sa.SA_OP_SAMPLE_PERM), device=dev, dtype=torch.uint8)
-        _, spw8_ms = time_op(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k, wss8), 10, 2)
+        _, spw8_ms = time_side(lambda: sa.sa_sample_perm(d8k, 1, 0, sampled8k, wss8), 10, 2)
         other.update({"sample_perm_ws_n32768_ms": spw_ms, "sample_perm_ws_n8192_ms": spw8_ms})
         del wss, wss8
         # RoPE on original positions for Q and K of the headline shape (out of place; table built once)
         table = torch.empty((wl.n, wl.d // 2, 2), device=dev, dtype=torch.float32)
         sa.sa_rope_table(wl.n, wl.d, 1e6, 0, table)
         Kr = torch.empty_like(K)
-        _, rp_ms = time_op(lambda: sa.sa_rope(desc, Q, K, table, Y2, Kr), max(10, args.steps // 4), 5)
+        _, rp_ms = time_side(lambda: sa.sa_rope(desc, Q, K, table, Y2, Kr), max(10, args.steps // 4), 5)
         rp_bytes = 2 * (Q.numel() + K.numel()) * 2
         other.update({"rope_qk_ms": rp_ms, "rope_qk_GBps": rp_bytes / (rp_ms * 1e-3) / 1e9,
                       "rope_qk_frac_hbm": rp_bytes / (rp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
@@ -373,7 +381,7 @@ def main():
         def rope_then_attention():
             sa.sa_rope(desc, None, K, table, None, Kr)
             sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, LSE)
-        _, rf_ms = time_op(rope_then_attention, max(10, args.steps // 4), 5)
+        _, rf_ms = time_side(rope_then_attention, max(10, args.steps // 4), 5)
         other.update({"rope_k_plus_fwd_rope_ms": rf_ms, "rope_qk_plus_fwd_ms": rp_ms + ms_per_step})
         del Y2, Kr, table
         # backward of the headline shape (not a workload of the paper, which trains at d = 64): dQ, dK, dV from dY
@@ -381,7 +389,7 @@ def main():
         dQh, dKh, dVh = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
         wsh = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=dev, dtype=torch.uint8)
         sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
-        _, bw_ms = time_op(lambda: sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, LSE, None, dYh,
+        _, bw_ms = time_side(lambda: sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, LSE, None, dYh,
                                              dQh, dKh, dVh, None, None, wsh), max(5, args.steps // 20), 2)
         other.update({"sa_bwd_headline_shape_ms": bw_ms,
                       "sa_fwdbwd_headline_shape_band_tflops": 3.5 * band_flop / ((ms_per_step + bw_ms) * 1e-3) / 1e12})
