@@ -178,9 +178,11 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   // logical chunk (l % CPR) ^ swz(row) of the row the index ring names.  The swizzle depends on the low
   // four bits of the row only, which are the same for every instruction of the lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-  const int ld_row = wave * C::RPI + lane / C::CPR;  // row of the lane in instruction 0
-  const uint32_t ld_chunk_off = (uint32_t)(((lane % C::CPR) ^ swz<D>(ld_row)) * 16);
   auto load_tile = [&](const int tile, const int buf) {
+    int le = lane;  // the lane's row and chunk are formed again from a copy the optimiser cannot hoist
+    asm volatile("" : "+v"(le));
+    const int ld_row = wave * C::RPI + le / C::CPR;
+    const uint32_t ld_chunk_off = (uint32_t)(((le % C::CPR) ^ swz<D>(ld_row)) * 16);
     const int* idx = ring + (tile & (C::RING - 1)) * BN;
     int ridx[C::NI];
 #pragma unroll
@@ -251,10 +253,6 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   }
 
 
-  // ---- per-lane window constants: key t is visible iff 0 <= t - s + Ll <= LRl (unsigned compare)
-  const int Ll = circular ? L : min(L, max(s, 0));
-  const int Rl = circular ? R : min(R, max(n - 1 - s, 0));
-  const unsigned LRl = (unsigned)(Ll + Rl);
 
   // ---- per-lane element offsets of the operand reads inside a swizzled tile (without the block's rows)
   int koff[D / 16], voff[D / 32][2];
@@ -279,7 +277,12 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
     __syncthreads();
     if (tid < BN) {  // indices: tile+3 -> ring, tile+4 -> register
       ring[((tile + 3) & (C::RING - 1)) * BN + tid] = pk_reg;
-      if (CAUSAL == CAUSAL_I16) ring16[((tile + 3) & (C::RING - 1)) * BN + pos16] = (short)(pk_reg - 32768);
+      if (CAUSAL == CAUSAL_I16) {
+        int te = tid;  // the position is formed again from a copy the optimiser cannot hoist, not kept in a register
+        asm volatile("" : "+v"(te));
+        const int pos = (te & 32) | ((te & 4) << 2) | ((te >> 1) & 12) | (te & 3);
+        ring16[((tile + 3) & (C::RING - 1)) * BN + pos] = (short)(pk_reg - 32768);
+      }
       if (tile + 4 < ntiles) pk_reg = tile_row_orig(tile + 4);
     }
     if (tile + 1 < ntiles) load_tile(tile + 1, buf ^ 1);
@@ -342,7 +345,15 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
       if (!act[kb]) continue;
       if (CAUSAL == CAUSAL_I32) causal_to_neg_inf(sacc[kb], kb);
       if (!inside[kb]) {
-        const int base = t0 + 32 * kb + 4 * g2 - s + Ll;
+        // per-lane window constants: key t is visible iff 0 <= t - s + Ll <= LRl (unsigned compare).  Formed
+        // here, in the few blocks at the edge of the band, from a copy of s the optimiser cannot hoist.
+        int se = lane;
+        asm volatile("" : "+v"(se));
+        se = s_w0 + (se & 31);
+        const int Ll = circular ? L : min(L, max(se, 0));
+        const int Rl = circular ? R : min(R, max(n - 1 - se, 0));
+        const unsigned LRl = (unsigned)(Ll + Rl);
+        const int base = t0 + 32 * kb + 4 * g2 - se + Ll;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const unsigned u = (unsigned)(base + 8 * (i / 4) + (i % 4));
@@ -391,9 +402,13 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
       if (CAUSAL == CAUSAL_I16) {
         // pair e of the lane = accumulators 2e, 2e+1; the ring keeps their biased indices as one dword
         typedef short s16x2 __attribute__((ext_vector_type(2)));
-        const s16x2 oq1 = {(short)(orig_q + 1 - 32768), (short)(orig_q + 1 - 32768)};
+        int oqe = orig_q;  // a copy the optimiser cannot hoist: the packed constant is formed per block, not kept
+        asm volatile("" : "+v"(oqe));
+        const s16x2 oq1 = {(short)(oqe + 1 - 32768), (short)(oqe + 1 - 32768)};
         const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
-        const uint32_t* pk16 = reinterpret_cast<const uint32_t*>(ring16 + (tile & (C::RING - 1)) * BN) + 16 * kb + 8 * g2;
+        int ge = lane;
+        asm volatile("" : "+v"(ge));
+        const uint32_t* pk16 = reinterpret_cast<const uint32_t*>(ring16 + (tile & (C::RING - 1)) * BN) + 16 * kb + 8 * (ge >> 5);
         const u32x4 ia = *reinterpret_cast<const u32x4*>(pk16), ib = *reinterpret_cast<const u32x4*>(pk16 + 4);
         u32x4 w[2];
 #pragma unroll
@@ -443,14 +458,14 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   const float inv_l = 1.f / l_tot;
   const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
   const size_t my_row = head_row0 + orig_q;  // this lane's output row (valid when s < n)
-  if (p.LSE && g2 == 0 && s < n) p.LSE[my_row] = m_ref * p.scale + __logf(l_tot);
+  if (p.LSE && g2 == 0 && s_w0 + c32 < n) p.LSE[my_row] = m_ref * p.scale + __logf(l_tot);
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[db][i] *= inv_l;
 
   // accumulator (db, 4mq..4mq+3) of a lane = elements 32db + 8mq + 4g2 .. +3 of its row
-  if (GATED && p.Y_f32_out && s < n) {  // first branch of the gated forward: keep an unrounded copy
+  if (GATED && p.Y_f32_out && s_w0 + c32 < n) {  // first branch of the gated forward: keep an unrounded copy
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -463,6 +478,9 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::QSTR;
   auto stage_and_store = [&](const f32x16* acc, void* dst_tensor) {
     __syncthreads();  // the staging area is free (last tile consumed / previous staging pass stored)
+    int le = lane;  // the lane's staging address is formed here, from a copy the optimiser cannot trace back to
+    asm volatile("" : "+v"(le));  // the prologue's (equal) one, which it would otherwise keep across the tile loop
+    bf16_t* mine = Os + (le & 31) * C::QSTR + 4 * (le >> 5);
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -470,7 +488,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
         u32x2 w;
         w[0] = pack_bf16(acc[db][4 * mq + 0], acc[db][4 * mq + 1]);
         w[1] = pack_bf16(acc[db][4 * mq + 2], acc[db][4 * mq + 3]);
-        *reinterpret_cast<u32x2*>(Os + c32 * C::QSTR + 32 * db + 8 * mq + 4 * g2) = w;
+        *reinterpret_cast<u32x2*>(mine + 32 * db + 8 * mq) = w;
       }
     wave_lds_sync();  // the staging rows are this wave's own
     int dst[NP];
@@ -490,7 +508,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   if (p.Y) stage_and_store(oacc, p.Y);
   if (GATED && p.gate_mode) {
     // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other, formed in fp32 and rounded once
-    const size_t r = s < n ? my_row : head_row0;
+    const size_t r = s_w0 + c32 < n ? my_row : head_row0;
     float ga = 0.f, gb = 0.f;
     if (!p.gate_per_dim) {
       ga = sigmoidf_exact(load_gate(p.gate_this, r, p.gate_f32));
