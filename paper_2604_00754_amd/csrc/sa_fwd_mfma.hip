@@ -178,11 +178,9 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   // logical chunk (l % CPR) ^ swz(row) of the row the index ring names.  The swizzle depends on the low
   // four bits of the row only, which are the same for every instruction of the lane.
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int ld_row = wave * C::RPI + lane / C::CPR;  // row of the lane in instruction 0
+  const uint32_t ld_chunk_off = (uint32_t)(((lane % C::CPR) ^ swz<D>(ld_row)) * 16);
   auto load_tile = [&](const int tile, const int buf) {
-    int le = lane;  // the lane's row and chunk are formed again from a copy the optimiser cannot hoist
-    asm volatile("" : "+v"(le));
-    const int ld_row = wave * C::RPI + le / C::CPR;
-    const uint32_t ld_chunk_off = (uint32_t)(((le % C::CPR) ^ swz<D>(ld_row)) * 16);
     const int* idx = ring + (tile & (C::RING - 1)) * BN;
     int ridx[C::NI];
 #pragma unroll
