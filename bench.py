@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per sa_fwd launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE scaled
 # by 2.000, WRITE_SIZE by 1.000 against a 1 GiB copy); see profiles/fwd_mfma_bf16_d128_qwen3_8b_prefill_32k.md
-MEASURED_TRAFFIC_BYTES = 404400 * 1024 + 340000 * 1024
+MEASURED_TRAFFIC_BYTES = 396600 * 1024 + 303800 * 1024
 
 
 def band_slots(n, w, window):
