@@ -194,8 +194,10 @@ sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void*
  * branches and must agree in every other field.  gate_sa / gate_swa: logits, [B,Hq,n] or
  * [B,Hq,n,d] per sa->gate_per_dim, of sa->gate_dtype.
  * Y_sa, Y_swa (branch outputs, needed by the backward), LSE_sa, LSE_swa may each be NULL.
- * ws: sa_workspace_bytes(sa, SA_OP_GATED_FWD) bytes (bf16: the first branch is kept in fp32 there so
- * that the gated sum is rounded once; fp32: none needed). */
+ * ws: sa_workspace_bytes(sa, SA_OP_GATED_FWD) bytes, needed only in the bf16 configuration when Y_swa is
+ * NULL (the sliding-window branch's rows are kept there).  In the bf16 configuration the sum of Eq. 5 is
+ * formed in fp32 from the stochastic branch's fp32 accumulators and the sliding-window branch's rows as
+ * the bf16 tensor they are stored as, and rounded once. */
 sa_status gated_sa_swa_fwd(const sa_desc* sa, const sa_desc* swa,
                            const void* Q, const void* K, const void* V, const int32_t* perm,
                            const void* gate_sa, const void* gate_swa,

@@ -114,7 +114,7 @@ DualBwdWorkspace dual_bwd_workspace(const sa_desc* c) {
 // The bf16 gated forward keeps the first branch's rows in fp32 until the gated sum is rounded.
 size_t gated_fwd_workspace(const sa_desc* c) {
   if (c->dtype != SA_BF16) return 0;
-  return align256((size_t)c->B * c->Hq * c->n * c->d * sizeof(float));
+  return align256((size_t)c->B * c->Hq * c->n * c->d * 2);  // the first branch's rows, when the caller does not keep them
 }
 
 sa_status hip_status(hipError_t e) { return e == hipSuccess ? SA_OK : (e == hipErrorNotSupported ? SA_ERR_UNSUPPORTED : SA_ERR_HIP); }
@@ -362,16 +362,15 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (s != SA_OK) return s;
   if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
   if (!Q || !K || !V || !Y || !gate_sa || !gate_swa) return SA_ERR_NULL;
-  const size_t need = gated_fwd_workspace(sa_d);
-  if (need && (!ws || ws_bytes < need)) return SA_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
   const bool bf16 = sa_d->dtype == SA_BF16;
+  const size_t need = gated_fwd_workspace(sa_d);
+  if (bf16 && !Y_swa && (!ws || ws_bytes < need)) return SA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
 
-  // sliding-window branch first (Alg. 2).  bf16: rows also go to the workspace in fp32 (and to Y_swa
-  // if the caller keeps it); fp32: rows go to Y_swa, or to Y itself when Y_swa is not wanted.
+  // sliding-window branch first (Alg. 2).  Its rows go to Y_swa if the caller keeps them, else to the
+  // workspace (bf16) or to Y itself (fp32: the second pass reads a row before it overwrites it).
   Pass a = make_pass(swa_d, Q, K, V, nullptr);
-  a.Y = bf16 ? Y_swa : (Y_swa ? Y_swa : Y);
-  a.Y_f32_out = bf16 ? reinterpret_cast<float*>(ws) : nullptr;
+  a.Y = Y_swa ? Y_swa : (bf16 ? ws : Y);
   a.LSE = LSE_swa;
   hipError_t e = run_fwd(swa_d, a, st);
   if (e != hipSuccess) return hip_status(e);
@@ -385,8 +384,7 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   b.gate_f32 = sa_d->gate_dtype == SA_F32;
   b.gate_this = gate_sa;
   b.gate_other = gate_swa;
-  b.Y_other = bf16 ? nullptr : a.Y;
-  b.Y_other_f32 = bf16 ? reinterpret_cast<const float*>(ws) : nullptr;
+  b.Y_other = a.Y;
   b.Yout = Y;
   return hip_status(run_fwd(sa_d, b, st));
 }

@@ -38,9 +38,7 @@ struct Pass {
   int gate_per_dim, gate_f32;
   const void* gate_this;
   const void* gate_other;
-  const void* Y_other;  // the other branch's rows [B,Hq,n,d] in the tensor dtype (fp32 path; may alias Yout)
-  const float* Y_other_f32;  // bf16 path: the other branch's rows kept in fp32 [B,Hq,n,d]
-  float* Y_f32_out;     // bf16 path, first branch of the gated forward: also write the rows in fp32 here
+  const void* Y_other;  // the other branch's rows [B,Hq,n,d] in the tensor dtype (fp32 path: may alias Yout)
   void* Yout;           // gated sum
   // backward
   const void* dO;       // gradient w.r.t. this branch's output [B,Hq,n,d]

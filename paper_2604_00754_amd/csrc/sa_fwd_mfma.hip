@@ -87,9 +87,9 @@ __device__ __forceinline__ u32x4 load_row_chunk_once(const bf16_t* head, int row
 enum { CAUSAL_NONE = 0, CAUSAL_I32 = 1, CAUSAL_I16 = 2 };
 
 // PERM = false: identity permutation (plain windowed attention); no index loads are generated.
-// GATED = true: the variants of the gated forward (an unrounded fp32 copy of the result, or the gated sum of
-// Eq. 5 in the epilogue); they need more registers after the tile loop, so at d = 64 they run three
-// workgroups per CU where the plain kernel runs four.
+// GATED = true: the second branch of the gated forward, with the gated sum of Eq. 5 in the epilogue; it needs
+// more registers after the tile loop, so at d = 64 it runs three workgroups per CU where the plain kernel
+// runs four.
 template <int D, bool PERM, int CAUSAL, bool GATED>
 __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 : FWD_WGS128)) void fwd_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                               const int hshift) {
@@ -463,16 +463,6 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
     for (int i = 0; i < 16; ++i) oacc[db][i] *= inv_l;
 
   // accumulator (db, 4mq..4mq+3) of a lane = elements 32db + 8mq + 4g2 .. +3 of its row
-  if (GATED && p.Y_f32_out && s_w0 + c32 < n) {  // first branch of the gated forward: keep an unrounded copy
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int mq = 0; mq < 4; ++mq) {
-        const f32x4 v = {oacc[db][4 * mq], oacc[db][4 * mq + 1], oacc[db][4 * mq + 2], oacc[db][4 * mq + 3]};
-        *reinterpret_cast<f32x4*>(p.Y_f32_out + my_row * D + 32 * db + 8 * mq + 4 * g2) = v;
-      }
-  }
-
   bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::QSTR;
   auto stage_and_store = [&](const f32x16* acc, void* dst_tensor) {
     __syncthreads();  // the staging area is free (last tile consumed / previous staging pass stored)
@@ -505,7 +495,8 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 
   if (p.Y) stage_and_store(oacc, p.Y);
   if (GATED && p.gate_mode) {
-    // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other, formed in fp32 and rounded once
+    // Eq. 5: Y = sig(gamma_this) * Y_this + sig(gamma_other) * Y_other, formed in fp32: this branch enters
+    // with its fp32 accumulators, the other one as the bf16 tensor it was stored as
     const size_t r = s_w0 + c32 < n ? my_row : head_row0;
     float ga = 0.f, gb = 0.f;
     if (!p.gate_per_dim) {
@@ -517,7 +508,8 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 #pragma unroll
       for (int mq = 0; mq < 4; ++mq) {
         const size_t e0 = r * D + 32 * db + 8 * mq + 4 * g2;
-        const f32x4 o = *reinterpret_cast<const f32x4*>(p.Y_other_f32 + e0);
+        const u32x2 ob = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16_t*>(p.Y_other) + e0);
+        const float o[4] = {bf16lo(ob[0]), bf16hi(ob[0]), bf16lo(ob[1]), bf16hi(ob[1])};
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
           if (p.gate_per_dim) {
@@ -551,7 +543,7 @@ hipError_t launch_t(const Pass& p, hipStream_t st) {
     if (gated) hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_, true>), grid, block, 0, st, p, num_qt, total, hshift); \
     else hipLaunchKernelGGL((fwd_mfma_bf16_kernel<D, PERM_, MODE_, false>), grid, block, 0, st, p, num_qt, total, hshift);      \
   } while (0)
-  const bool gated = p.gate_mode != 0 || p.Y_f32_out != nullptr;
+  const bool gated = p.gate_mode != 0;
   if (p.perm) {
     if (mode == CAUSAL_NONE) SA_LAUNCH_FWD(true, CAUSAL_NONE);
     else if (mode == CAUSAL_I16) SA_LAUNCH_FWD(true, CAUSAL_I16);
@@ -573,7 +565,7 @@ hipError_t launch_fwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (p.win.L < 0 || p.win.R < 0 || p.win.L >= p.n || p.win.R >= p.n) return hipErrorInvalidValue;
   if (p.win.circular && p.win.L + p.win.R + 1 > p.n) return hipErrorInvalidValue;
   if ((long)p.n * p.d * 2 >= (1L << 31)) return hipErrorNotSupported;  // 32-bit row offsets inside a head
-  if (p.gate_mode && (!p.gate_this || !p.gate_other || !p.Y_other_f32 || !p.Yout)) return hipErrorInvalidValue;
+  if (p.gate_mode && (!p.gate_this || !p.gate_other || !p.Y_other || !p.Yout)) return hipErrorInvalidValue;
   if (p.d == 64) return launch_t<64>(p, st);
   if (p.d == 128) return launch_t<128>(p, st);
   return hipErrorNotSupported;

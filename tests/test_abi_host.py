@@ -68,7 +68,7 @@ def test_workspace_sizes_and_checks():
     d = good()
     rows = d.B * d.Hq * d.n
     assert sa.sa_workspace_bytes(d, sa.SA_OP_FWD) == 0
-    assert sa.sa_workspace_bytes(d, sa.SA_OP_GATED_FWD) >= rows * d.d * 4
+    assert sa.sa_workspace_bytes(d, sa.SA_OP_GATED_FWD) >= rows * d.d * 2   # the first branch as a bf16 tensor
     f32 = good()
     f32.dtype = sa.SA_F32
     assert sa.sa_workspace_bytes(f32, sa.SA_OP_GATED_FWD) == 0
