@@ -424,19 +424,29 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   pr.dO_a = gated ? base + w.off_dOa : nullptr;
   pr.dO_b = gated ? base + w.off_dOb : nullptr;
   pr.dgate_a = dgate_sa; pr.dgate_b = dgate_swa;
+  // bf16, one gate per (head, token): the gate goes into the per-row scalars, both branches run on dY itself
+  // (the two shifted LSE vectors take the place of the first branch gradient in the workspace)
+  const bool fold = gated && !sa_d->gate_per_dim && sa_d->dtype == SA_BF16;
+  pr.fold = fold;
+  pr.lse_a = LSE_sa; pr.lse_b = LSE_swa;
+  pr.L_a = fold ? reinterpret_cast<float*>(base + w.off_dOa) : nullptr;
+  pr.L_b = fold ? pr.L_a + (size_t)pr.rows : nullptr;
   hipError_t e = sa::launch_bwd_prepare(pr, st);
   if (e != hipSuccess) return hip_status(e);
 
   if (gated) {
     Pass a = make_pass(swa_d, Q, K, V, nullptr);
-    a.dO = pr.dO_b; a.lse_in = LSE_swa; a.Dsum = pr.D_b;
+    a.dO = fold ? dY : pr.dO_b;
+    a.lse_in = fold ? pr.L_b : LSE_swa;
+    a.Dsum = pr.D_b;
     a.dQ = dQ; a.dK = dK; a.dV = dV; a.accumulate = 0;
     e = run_bwd(swa_d, a, st);
     if (e != hipSuccess) return hip_status(e);
   }
   Pass b = make_pass(sa_d, Q, K, V, perm);
-  b.dO = gated ? pr.dO_a : dY;
-  b.lse_in = LSE_sa; b.Dsum = pr.D_a;
+  b.dO = gated && !fold ? pr.dO_a : dY;
+  b.lse_in = fold ? pr.L_a : LSE_sa;
+  b.Dsum = pr.D_a;
   b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = gated ? 1 : 0;
   return hip_status(run_bwd(sa_d, b, st));
 }

@@ -95,6 +95,14 @@ struct Prep {
   void* dO_a; void* dO_b;                      // gated only
   float* D_a; float* D_b;
   void* dgate_a; void* dgate_b;
+  // gated with one gate per (head, token) and fold != 0: the gate is folded into the per-row scalars instead
+  // of into a copy of dY.  With g = sigmoid(gamma_x): dO_x = g dY, so P^T dO_x = (g P)^T dY and
+  // dS_x = P (dO_x V^T - D_x) = (g P) (dY V^T - E_x) with E_x = rowsum(dY * Y_x) = D_x / g.  The backward
+  // kernels then run on dY itself with LSE_x - ln g in place of LSE_x (which turns P into g P) and E_x in
+  // place of D_x; g = 0 gives +inf and P = 0.  D_a / D_b receive E_x, L_a / L_b the shifted LSE.
+  int fold;
+  const float* lse_a; const float* lse_b;
+  float* L_a; float* L_b;
 };
 hipError_t launch_bwd_prepare(const Prep& p, hipStream_t st);
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t st);

@@ -277,6 +277,23 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(Prep p) {
     ra = fmaf(dy[k], ya[k], ra);
     rb = fmaf(dy[k], yb[k], rb);
   }
+  if (p.fold) {  // one gate per row: E_x, LSE_x - ln g_x, dgamma_x; no copy of dY
+    ra = group_sum<LPR>(ra);
+    rb = group_sum<LPR>(rb);
+    if (valid && sub == 0) {
+      const float xa = load_gate(p.gate_a, r, p.gate_f32), xb = load_gate(p.gate_b, r, p.gate_f32);
+      // -ln sigmoid(x) = ln(1 + e^-x), evaluated without cancellation on either side
+      const float na = xa > 0.f ? log1pf(__expf(-xa)) : -xa + log1pf(__expf(xa));
+      const float nb = xb > 0.f ? log1pf(__expf(-xb)) : -xb + log1pf(__expf(xb));
+      p.D_a[r] = ra;
+      p.D_b[r] = rb;
+      p.L_a[r] = p.lse_a[r] + na;
+      p.L_b[r] = p.lse_b[r] + nb;
+      store_gate(p.dgate_a, r, p.gate_f32, ga[0] * (1.f - ga[0]) * ra);
+      store_gate(p.dgate_b, r, p.gate_f32, gb[0] * (1.f - gb[0]) * rb);
+    }
+    return;
+  }
   sa = group_sum<LPR>(sa);
   sb = group_sum<LPR>(sb);
   if (valid && sub == 0) {
