@@ -121,6 +121,15 @@ def test_bwd_bf16_query_heads_of_a_group_share_a_workgroup(Hq, Hkv):
     run_bwd(1, Hq, Hkv, 31, 64, 8, CIRC, 1, "bf16", seed=83 + Hq)
 
 
+@pytest.mark.parametrize("n", [1, 33, 64, 65, 127, 128, 129, 191, 257])
+def test_bwd_bf16_slot_counts_around_tile_edges(n):
+    """Sequence lengths around multiples of the 32-slot blocks and of the 64- / 128-slot streamed tiles."""
+    for d in (64, 128):
+        run_bwd(1, 4, 1, n, d, 40, CIRC, 1, "bf16", seed=95 + d)
+        run_bwd(1, 2, 2, n, d, 2 * n + 3, CIRC, 1, "bf16", perm_H=2, seed=96 + d)
+        run_bwd(1, 1, 1, n, d, 64, ONE, 1, "bf16", identity=True, seed=97 + d)
+
+
 def test_bwd_bf16_per_head_perm_with_grouped_heads():
     run_bwd(2, 8, 2, 600, 64, 128, CIRC, 1, "bf16", perm_B=2, perm_H=8, seed=30)
     run_bwd(1, 4, 4, 600, 64, 128, CIRC, 1, "bf16", perm_H=4, seed=31)

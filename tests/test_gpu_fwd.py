@@ -94,6 +94,17 @@ def test_bf16_query_heads_of_a_group_share_a_workgroup(Hq, Hkv):
     run_fwd(1, Hq, Hkv, 31, 64, 8, CIRC, 1, "bf16", seed=64 + Hq)                  # less than one wave of slots
 
 
+@pytest.mark.parametrize("n", [1, 2, 32, 33, 63, 64, 65, 96, 97, 159, 160, 161, 255, 257])
+def test_bf16_slot_counts_around_tile_edges(n):
+    """Sequence lengths around multiples of the 32-slot blocks and of the 32- / 64-key tiles (d = 128 / 64),
+    with windows below, at and above n, each window kind, with and without shared workgroups."""
+    for d in (64, 128):
+        run_fwd(1, 4, 1, n, d, 40, CIRC, 1, "bf16", seed=90 + d)                     # four heads per workgroup
+        run_fwd(1, 2, 2, n, d, 2 * n + 3, CIRC, 1, "bf16", perm_H=2, seed=91 + d)   # window covers the ring
+        run_fwd(1, 2, 1, n, d, 33, LIN, 0, "bf16", seed=92 + d)                     # two heads per workgroup
+        run_fwd(1, 1, 1, n, d, 64, ONE, 1, "bf16", identity=True, use_swa_entry=True, seed=93 + d)
+
+
 def test_bf16_later_keys_dominate():
     """Scores of later (causally masked) keys far above the visible ones: the packed 16-bit mask clears
     their probabilities after the exponential, so they must neither move the softmax reference nor leak
