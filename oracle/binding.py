@@ -230,3 +230,15 @@ def dual_path_bwd(sa, swa, Q, K, V, perm, Wsa, Wswa, dY):
     a = sa_bwd(sa, Q, K, V, perm, g["dYsa"])
     b = sa_bwd(swa, Q, K, V, None, g["dYswa"])
     return dict(dQ=a[0] + b[0], dK=a[1] + b[1], dV=a[2] + b[2], dWsa=g["dWsa"], dWswa=g["dWswa"])
+
+
+def decode_fwd(c, q, K, V, length):
+    """Decoding step of Sec. 4.2: one query per (b, hq) over rows 0..length-1 of the caches.
+    Returns (Y [B,Hq,d], LSE [B,Hq])."""
+    ks = (c.B, c.Hkv, c.n, c.d)
+    q, K, V = _f64(q, (c.B, c.Hq, c.d)), _f64(K, ks), _f64(V, ks)
+    Y = np.empty((c.B, c.Hq, c.d), np.float64)
+    L = np.empty((c.B, c.Hq), np.float64)
+    _check(lib().orc_decode_fwd(C.byref(c), _p(q), _p(K), _p(V), C.c_int32(int(length)), _p(Y), _p(L)),
+           "orc_decode_fwd")
+    return Y, L

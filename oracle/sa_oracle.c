@@ -651,3 +651,46 @@ int orc_gate_proj_bwd(const orc_desc* c, const double* Ysa, const double* Yswa,
   if (dual) gate_proj_bwd_branch(c, Yswa, Wswa, dY, dYswa, dWswa);
   return 0;
 }
+
+/* ------------------------------------------------------------------ decode */
+
+/* Sec. 4.2 (inference setting): the sparse modes are used while the prompt is
+ * processed; each generated token then attends to the WHOLE cache.  One query
+ * row per (b, hq), plain softmax attention (Eq. 1 with the window covering
+ * every cached row) over rows 0..len-1 of the caches:
+ *   z_j = scale <q, K_j>,  LSE = log sum_j e^{z_j},  Y = sum_j e^{z_j - LSE} V_j.
+ * q [B,Hq,d], K,V [B,Hkv,n,d] (n = capacity), Y [B,Hq,d], LSE [B,Hq] or NULL. */
+int orc_decode_fwd(const orc_desc* c, const double* q, const double* K, const double* V,
+                   int32_t len, double* Y, double* LSE) {
+  if (!desc_ok(c) || !q || !K || !V || !Y) return -1;
+  if (len < 1 || len > c->n) return -2;
+  const int g = c->Hq / c->Hkv;
+  const double scale = softmax_scale(c);
+  for (int b = 0; b < c->B; ++b) {
+    for (int hq = 0; hq < c->Hq; ++hq) {
+      const int hk = hq / g;
+      const double* qr = q + ((size_t)b * c->Hq + hq) * c->d;
+      const double* Kh = K + ((size_t)b * c->Hkv + hk) * (size_t)c->n * c->d;
+      const double* Vh = V + ((size_t)b * c->Hkv + hk) * (size_t)c->n * c->d;
+      double* z = (double*)malloc((size_t)len * sizeof(double));
+      if (!z) return -3;
+      double zmax = -INFINITY;
+      for (int j = 0; j < len; ++j) {
+        z[j] = scale * dot(qr, Kh + (size_t)j * c->d, c->d);
+        if (z[j] > zmax) zmax = z[j];
+      }
+      double sum = 0.0;
+      for (int j = 0; j < len; ++j) sum += exp(z[j] - zmax);
+      const double lse = zmax + log(sum);
+      double* y = Y + ((size_t)b * c->Hq + hq) * c->d;
+      for (int e = 0; e < c->d; ++e) y[e] = 0.0;
+      for (int j = 0; j < len; ++j) {
+        const double pj = exp(z[j] - lse);
+        for (int e = 0; e < c->d; ++e) y[e] += pj * Vh[(size_t)j * c->d + e];
+      }
+      if (LSE) LSE[(size_t)b * c->Hq + hq] = lse;
+      free(z);
+    }
+  }
+  return 0;
+}

@@ -126,6 +126,13 @@ int orc_gate_proj_bwd(const orc_desc* c, const double* Ysa, const double* Yswa,
                       const double* Wsa, const double* Wswa, const double* dY,
                       double* dYsa, double* dYswa, double* dWsa, double* dWswa);
 
+/* Decoding step of the inference setting (Sec. 4.2): one query row per (b, hq) attends to rows
+ * 0..len-1 of the K/V caches with plain softmax attention (Eq. 1, every cached row visible).
+ * q [B,Hq,d], K,V [B,Hkv,n,d] with n the capacity, 1 <= len <= n, Y [B,Hq,d], LSE [B,Hq] (may be
+ * NULL).  w, window, causal and the perm fields of the descriptor are not used. */
+int orc_decode_fwd(const orc_desc* c, const double* q, const double* K, const double* V,
+                   int32_t len, double* Y, double* LSE);
+
 #ifdef __cplusplus
 }
 #endif

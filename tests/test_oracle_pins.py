@@ -692,3 +692,49 @@ def test_rope_is_a_rotation_with_relative_position_scores_and_its_inverse_is_the
         np.testing.assert_allclose(yt.detach().numpy(), rq, atol=1e-14)
         (yt * torch.tensor(g)).sum().backward()
         np.testing.assert_allclose(R.rope(g, interleaved=il, pos0=11, inverse=True), t.grad.numpy(), atol=1e-13)
+
+
+# ------------------------------------------------------------------ decoding step of Sec. 4.2
+
+def test_decode_step_against_sdpa_the_prefill_row_and_closed_forms():
+    """The full-cache decoding step is pinned to a library routine (torch SDPA in fp64 with the
+    grouped K/V heads repeated), to the last row of full causal attention (the row the prompt pass would have
+    produced for that token) and to two closed forms."""
+    B, Hq, Hkv, n, d, length = 2, 6, 2, 29, 8, 23
+    g = Hq // Hkv
+    c = orc.desc(B, Hq, Hkv, n, d, 1)
+    q, K, V = rnd((B, Hq, d), 601), rnd((B, Hkv, n, d), 602), rnd((B, Hkv, n, d), 603)
+    Y, L = orc.decode_fwd(c, q, K, V, length)
+    Kr, Vr = np.repeat(K[:, :, :length], g, axis=1), np.repeat(V[:, :, :length], g, axis=1)
+    Yt = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q[:, :, None, :]), torch.from_numpy(Kr), torch.from_numpy(Vr)).numpy()[:, :, 0]
+    np.testing.assert_allclose(Y, Yt, atol=1e-12)
+    z = np.einsum("bhd,bhjd->bhj", q, Kr) / math.sqrt(d)
+    np.testing.assert_allclose(L, np.log(np.exp(z).sum(-1)), atol=1e-12)
+    # rows beyond `length` are never read: poison them
+    K2, V2 = K.copy(), V.copy()
+    K2[:, :, length:], V2[:, :, length:] = np.nan, np.nan
+    Y2, L2 = orc.decode_fwd(c, q, K2, V2, length)
+    assert np.array_equal(Y2, Y) and np.array_equal(L2, L)
+    # hand-off: the query of token length-1 over a cache of `length` rows is row length-1 of full causal
+    # attention over the prompt (one-sided window with w >= n, identity permutation)
+    Q = rnd((B, Hq, n, d), 604)
+    Yp, Lp = orc.sa_fwd(orc.desc(B, Hq, Hkv, n, d, n, orc.WIN_ONE_SIDED, 1), Q, K, V, None)
+    Yd, Ld = orc.decode_fwd(c, Q[:, :, length - 1], K, V, length)
+    np.testing.assert_allclose(Yd, Yp[:, :, length - 1], atol=1e-12)
+    np.testing.assert_allclose(Ld, Lp[:, :, length - 1], atol=1e-12)
+    # closed forms: q = 0 gives the mean of the cached values and LSE = ln(len); len = 1 returns V_0
+    Y0, L0 = orc.decode_fwd(c, np.zeros_like(q), K, V, length)
+    np.testing.assert_allclose(Y0, np.repeat(V[:, :, :length].mean(2), g, axis=1), atol=1e-13)
+    np.testing.assert_allclose(L0, math.log(length), atol=1e-13)
+    Y1, L1 = orc.decode_fwd(c, q, K, V, 1)
+    np.testing.assert_allclose(Y1, np.repeat(V[:, :, 0], g, axis=1), atol=1e-13)
+    np.testing.assert_allclose(L1, np.einsum("bhd,bhd->bh", q, np.repeat(K[:, :, 0], g, axis=1)) / math.sqrt(d),
+                               atol=1e-13)
+    # a given scale replaces 1/sqrt(d); invalid lengths are refused
+    cs = orc.desc(B, Hq, Hkv, n, d, 1, scale=0.37)
+    _, Ls = orc.decode_fwd(cs, q, K, V, length)
+    np.testing.assert_allclose(Ls, np.log(np.exp(0.37 * math.sqrt(d) * z).sum(-1)), atol=1e-12)
+    for bad in (0, n + 1):
+        with pytest.raises(ValueError):
+            orc.decode_fwd(c, q, K, V, bad)
