@@ -75,7 +75,8 @@ typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BW
                SA_OP_GATE_PROJ_BWD = 5,        /* sa_gate_proj_bwd, both branches */
                SA_OP_GATE_PROJ_BWD_SINGLE = 6, /* sa_gate_proj_bwd, single path   */
                SA_OP_DUAL_PATH_BWD = 7,        /* sa_dual_path_bwd                */
-               SA_OP_SAMPLE_PERM = 8           /* sa_sample_perm, O(n) path       */
+               SA_OP_SAMPLE_PERM = 8,          /* sa_sample_perm, O(n) path       */
+               SA_OP_DECODE = 9                /* sa_decode_fwd                   */
 } sa_op;
 
 const char* sa_status_string(sa_status s);
@@ -185,6 +186,18 @@ sa_status sa_dual_path_bwd(const sa_desc* sa, const sa_desc* swa, const void* Q,
                            const void* Y_swa, const void* G_sa, const void* G_swa, const float* LSE_sa,
                            const float* LSE_swa, const void* dY, void* dQ, void* dK, void* dV, void* dW_sa,
                            void* dW_swa, void* ws, size_t ws_bytes, void* stream);
+
+/* Decoding step of the inference setting (Sec. 4.2: the sparse modes are used for the prompt only, every
+ * generated token then attends to the whole K/V cache): one query row per (b, hq), plain softmax attention
+ * (Eq. 1 with every cached row visible) over rows 0..len-1 of the caches.  The caches hold K and V in the
+ * original order (the permutation never leaves sa_fwd).
+ * q [B,Hq,d], K, V [B,Hkv,n,d] with desc->n the capacity of the cache (the stride between heads), 1 <= len <= n
+ * (SA_ERR_SHAPE otherwise), Y [B,Hq,d], LSE [B,Hq] (fp32, may be NULL); all device memory, desc->dtype.
+ * desc->w, window, causal_orig and the perm and gate fields must be valid but are not used.  B*Hq <= 65535.
+ * ws: sa_workspace_bytes(desc, SA_OP_DECODE) bytes (partial results of the chunks the cache is cut into; the
+ * size depends on the capacity, not on len). */
+sa_status sa_decode_fwd(const sa_desc* desc, const void* q, const void* K, const void* V, int32_t len, void* Y,
+                        float* LSE, void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,

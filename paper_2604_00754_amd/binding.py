@@ -16,11 +16,12 @@ SA_BF16, SA_F32 = 0, 1
 SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
 SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD, SA_OP_SAMPLE_PERM = 5, 6, 7, 8
+SA_OP_DECODE = 9
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
            "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
-           "sa_rope_table", "sa_rope", "sa_fwd_rope")
+           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd")
 
 
 class sa_desc(C.Structure):
@@ -70,6 +71,8 @@ def _load():
     lib.sa_fwd_rope.argtypes = [dp, vp, vp, vp, ip, vp, C.c_int32, vp, vp, vp]
     lib.sa_rope.restype = C.c_int
     lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
+    lib.sa_decode_fwd.restype = C.c_int
+    lib.sa_decode_fwd.argtypes = [dp, vp, vp, vp, C.c_int32, vp, vp, vp, sz, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -173,6 +176,12 @@ def sa_rope_table(n, d, base, pos0, table):
 def sa_rope(desc, Q, K, table, Q_out, K_out, interleaved=0, inverse=0):
     _check(_lib.sa_rope(C.byref(desc), _ptr(Q), _ptr(K), _ptr(table), interleaved, inverse, _ptr(Q_out),
                         _ptr(K_out), _stream()), "sa_rope")
+
+
+def sa_decode_fwd(desc, q, K, V, length, Y, LSE, ws):
+    _check(_lib.sa_decode_fwd(C.byref(desc), _ptr(q), _ptr(K), _ptr(V), int(length), _ptr(Y), _ptr(LSE), _ptr(ws),
+                              (ws.numel() * ws.element_size()) if ws is not None else 0, _stream()),
+           "sa_decode_fwd")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsa.so")
-SOURCES = ["sa_api.hip", "sa_misc.hip", "sa_rowwise.hip", "sa_fwd_mfma.hip", "sa_bwd_mfma.hip", "sa_gate_proj.hip", "sa_rope.hip"]
+SOURCES = ["sa_api.hip", "sa_misc.hip", "sa_rowwise.hip", "sa_fwd_mfma.hip", "sa_bwd_mfma.hip", "sa_gate_proj.hip", "sa_rope.hip", "sa_decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

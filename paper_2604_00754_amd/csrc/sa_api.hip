@@ -156,6 +156,7 @@ size_t sa_workspace_bytes(const sa_desc* c, int op) {
     case SA_OP_GATE_PROJ_BWD_SINGLE: return sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, false);
     case SA_OP_DUAL_PATH_BWD: return dual_bwd_workspace(c).total;
     case SA_OP_SAMPLE_PERM: return sa::sample_perm_workspace_bytes(c->perm_B * c->perm_H, c->n);
+    case SA_OP_DECODE: return align256(sa::decode_workspace_bytes(c->B, c->Hq, c->Hkv, c->n, c->d));
     default: return 0;
   }
 }
@@ -189,6 +190,23 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   p.Y = Y;
   p.LSE = LSE;
   return hip_status(run_fwd(c, p, (hipStream_t)stream));
+}
+
+sa_status sa_decode_fwd(const sa_desc* c, const void* q, const void* K, const void* V, int32_t len, void* Y,
+                        float* LSE, void* ws, size_t ws_bytes, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!q || !K || !V || !Y) return SA_ERR_NULL;
+  if (len < 1 || len > c->n) return SA_ERR_SHAPE;
+  if ((long long)c->B * c->Hq > 65535) return SA_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < sa_workspace_bytes(c, SA_OP_DECODE)) return SA_ERR_WORKSPACE;
+  sa::Decode d = {};
+  d.q = q; d.K = K; d.V = V; d.Y = Y; d.LSE = LSE;
+  d.part = reinterpret_cast<float*>(ws);
+  d.B = c->B; d.Hq = c->Hq; d.Hkv = c->Hkv; d.n = c->n; d.d = c->d; d.len = len;
+  d.bf16 = c->dtype == SA_BF16;
+  d.scale = c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d);
+  return hip_status(sa::launch_decode(d, (hipStream_t)stream));
 }
 
 sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t* perm, void* ws, size_t ws_bytes,

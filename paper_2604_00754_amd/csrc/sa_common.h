@@ -81,6 +81,20 @@ hipError_t launch_rope_table(float* table, int n, int d, double base, int pos0, 
 hipError_t launch_rope_apply(const void* X, void* Xout, const float* table, int heads, int n, int d, int bf16,
                              int interleaved, int inverse, hipStream_t st);
 
+// sa_decode.hip: one query row per (b, hq) over rows 0..len-1 of the K/V caches (Sec. 4.2, decoding)
+struct Decode {
+  const void* q;   // [B,Hq,d]
+  const void* K;   // [B,Hkv,n,d], n = capacity
+  const void* V;
+  void* Y;         // [B,Hq,d]
+  float* LSE;      // [B,Hq], may be nullptr
+  float* part;     // decode_workspace_bytes(...) bytes
+  int B, Hq, Hkv, n, d, len, bf16;
+  float scale;
+};
+size_t decode_workspace_bytes(int B, int Hq, int Hkv, int n, int d);
+hipError_t launch_decode(const Decode& d, hipStream_t st);
+
 // helpers in sa_misc.hip
 hipError_t launch_check_perm(const int32_t* perm, int slices, int n, int* seen, int* flag,
                              hipStream_t st);

@@ -118,3 +118,26 @@ def test_binding_raises_with_status():
     with pytest.raises(sa.SaError) as e:
         sa._check(fwd(d), "sa_fwd")
     assert e.value.status == sa.SA_ERR_UNSUPPORTED
+
+
+def test_decode_step_arguments():
+    """sa_decode_fwd reports bad lengths, missing pointers and a short workspace before any launch."""
+    d = good()
+    lib = sa.raw()
+    need = sa.sa_workspace_bytes(d, sa.SA_OP_DECODE)
+    # one partial result of d + 2 floats per (b, hq) and chunk of the cache; chunks hold at most 1024 rows
+    assert need >= 2 * 8 * (128 + 2) * 4 and need % 256 == 0
+
+    def call(length=1000, q=FAKE, k=FAKE, v=FAKE, y=FAKE, ws=FAKE, ws_bytes=need):
+        return lib.sa_decode_fwd(C.byref(d), q, k, v, length, y, None, ws, ws_bytes, None)
+
+    for bad in (0, -1, 1001):
+        assert call(length=bad) == sa.SA_ERR_SHAPE
+    for kw in ("q", "k", "v", "y"):
+        assert call(**{kw: None}) == sa.SA_ERR_NULL
+    assert call(ws=None) == sa.SA_ERR_WORKSPACE
+    assert call(ws_bytes=need - 1) == sa.SA_ERR_WORKSPACE
+    assert lib.sa_decode_fwd(None, FAKE, FAKE, FAKE, 1, FAKE, None, FAKE, need, None) == sa.SA_ERR_NULL
+    # the workspace is sized by the capacity: it never grows when the descriptor's n shrinks
+    small = sa.make_desc(2, 8, 2, 500, 128, 256)
+    assert sa.sa_workspace_bytes(small, sa.SA_OP_DECODE) <= need
