@@ -394,6 +394,21 @@ def main():
         other.update({"sa_bwd_headline_shape_ms": bw_ms,
                       "sa_fwdbwd_headline_shape_band_tflops": 3.5 * band_flop / ((ms_per_step + bw_ms) * 1e-3) / 1e12})
         del dYh, dQh, dKh, dVh, wsh
+        # the decoding step that follows this prefill (Sec. 4.2): one new token per sequence over the whole
+        # 32K-row cache of the same heads; and a batch of 16 sequences with 8K-row caches
+        for name, Bd, nd in (("decode_32k", 1, wl.n), ("decode_b16_8k", 16, 8192)):
+            dd = sa.make_desc(Bd, wl.Hq, wl.Hkv, nd, wl.d, 2)
+            Kc = torch.randn((Bd, wl.Hkv, nd, wl.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+            Vc = torch.randn((Bd, wl.Hkv, nd, wl.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+            qd = torch.randn((Bd, wl.Hq, wl.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+            Yd = torch.empty_like(qd)
+            wsd = torch.empty(sa.sa_workspace_bytes(dd, sa.SA_OP_DECODE), device=dev, dtype=torch.uint8)
+            _, dc_ms = time_side(lambda: sa.sa_decode_fwd(dd, qd, Kc, Vc, nd, Yd, None, wsd),
+                                 max(10, args.steps // 4), 5)
+            dc_bytes = 2 * Kc.numel() * 2 + 2 * qd.numel() * 2
+            other.update({f"{name}_ms": dc_ms, f"{name}_GBps": dc_bytes / (dc_ms * 1e-3) / 1e9,
+                          f"{name}_frac_hbm": dc_bytes / (dc_ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+            del Kc, Vc, qd, Yd, wsd
         other.update(training_ops(sa, synth, dev, max(5, args.steps // 10)))
         other.update(long_prefill_ops(sa, synth, dev, max(3, args.steps // 40)))
 

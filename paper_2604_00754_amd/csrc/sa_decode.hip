@@ -14,8 +14,11 @@
 #include "sa_common.h"
 #include "sa_device.h"
 
+#ifndef DECODE_CHUNK
+#define DECODE_CHUNK 512         // cached rows per workgroup (per-workgroup set-up and merge cost favours long chunks)
+#endif
 #ifndef DECODE_TARGET_WGS
-#define DECODE_TARGET_WGS 1024   // chunks are shortened until the launch has at least this many workgroups
+#define DECODE_TARGET_WGS 512    // ... shortened (down to 64 rows) until the launch has at least this many workgroups
 #endif
 #ifndef DECODE_UNROLL
 #define DECODE_UNROLL 4          // wave-wide K (and V) loads in flight per loop iteration
@@ -78,6 +81,90 @@ struct Args {
 // exp2(a - b) where b is the reference maximum; a = b = -inf (nothing seen yet) gives 0
 __device__ __forceinline__ float exp2_rel(float a, float ref) { return exp2f(a - (ref == -INFINITY ? 0.f : ref)); }
 
+// Per-lane state of one lane group: the slice of 8 elements of the query rows, the running maximum (log2
+// domain), the running sum and the weighted V sum of every head.  The bf16 form keeps rows as packed pairs and
+// uses the two-element dot product instruction for both products (the weights are rounded to bf16 for the
+// second one, as in the prefill kernels); the fp32 form uses plain multiply-adds.
+template <typename T, int G, int U>
+struct Lane;
+
+template <int G, int U>
+struct Lane<float, G, U> {
+  float qf[G][8];
+  float kx[U][8], vx[U][8];
+  __device__ __forceinline__ void load_q(const float* p, int h, float scale_log2e) {
+    load8(p, qf[h]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[h][e] *= scale_log2e;
+  }
+  __device__ __forceinline__ void load_row(const float* k, const float* v, int u) {
+    load8(k, kx[u]);
+    load8(v, vx[u]);
+  }
+  __device__ __forceinline__ float partial_score(int h, int u) const {
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dot = fmaf(qf[h][e], kx[u][e], dot);
+    return dot;
+  }
+  static __device__ __forceinline__ float finish_score(float dot, float) { return dot; }
+  // acc = acc * corr + sum_u p[u] * V_u; returns sum_u p[u]
+  __device__ __forceinline__ float accumulate(float (&acc)[8], float corr, const float (&p)[U]) const {
+    float psum = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) psum += p[u];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[e] * corr;
+#pragma unroll
+      for (int u = 0; u < U; ++u) v = fmaf(p[u], vx[u][e], v);
+      acc[e] = v;
+    }
+    return psum;
+  }
+};
+
+template <int G, int U>
+struct Lane<bf16_t, G, U> {
+  static_assert(U % 2 == 0, "rows are consumed in pairs");
+  u32x4 q2[G];
+  u32x4 kx[U], vx[U];
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+  }
+  __device__ __forceinline__ void load_q(const bf16_t* p, int h, float) { q2[h] = *reinterpret_cast<const u32x4*>(p); }
+  __device__ __forceinline__ void load_row(const bf16_t* k, const bf16_t* v, int u) {
+    kx[u] = *reinterpret_cast<const u32x4*>(k);
+    vx[u] = *reinterpret_cast<const u32x4*>(v);
+  }
+  __device__ __forceinline__ float partial_score(int h, int u) const {
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dot = dot2(q2[h][i], kx[u][i], dot);
+    return dot;
+  }
+  static __device__ __forceinline__ float finish_score(float dot, float scale_log2e) { return dot * scale_log2e; }
+  __device__ __forceinline__ float accumulate(float (&acc)[8], float corr, const float (&p)[U]) const {
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= corr;
+#pragma unroll
+    for (int u = 0; u < U; u += 2) {
+      const uint32_t pp = pack_bf16(p[u], p[u + 1]);
+      psum += bf16lo(pp) + bf16hi(pp);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // (V_u[2i], V_u+1[2i]) and (V_u[2i+1], V_u+1[2i+1])
+        const uint32_t even = __builtin_amdgcn_perm(vx[u + 1][i], vx[u][i], 0x05040100u);
+        const uint32_t odd = __builtin_amdgcn_perm(vx[u + 1][i], vx[u][i], 0x07060302u);
+        acc[2 * i] = dot2(even, pp, acc[2 * i]);
+        acc[2 * i + 1] = dot2(odd, pp, acc[2 * i + 1]);
+      }
+    }
+    return psum;
+  }
+};
+
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
   constexpr int LPR = D / 8;          // lanes per row
@@ -98,15 +185,13 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
   const T* Kh = reinterpret_cast<const T*>(a.K) + head_off;
   const T* Vh = reinterpret_cast<const T*>(a.V) + head_off;
 
-  float qf[G][8], acc[G][8], m[G], l[G];
+  Lane<T, G, U> st;
+  float acc[G][8], m[G], l[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    load8(reinterpret_cast<const T*>(a.q) + ((size_t)b * a.Hq + hq0 + h) * D + sub * 8, qf[h]);
+    st.load_q(reinterpret_cast<const T*>(a.q) + ((size_t)b * a.Hq + hq0 + h) * D + sub * 8, h, a.scale_log2e);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      qf[h][e] *= a.scale_log2e;
-      acc[h][e] = 0.f;
-    }
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
     m[h] = -INFINITY;
     l[h] = 0.f;
   }
@@ -114,25 +199,20 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
   const int k0 = split * a.chunk;
   const int k1 = min(a.len, k0 + a.chunk);   // k0 < k1 <= len by the launch geometry
   for (int it = k0; it < k1; it += STEP * U) {
-    float kx[U][8], vx[U][8];
     bool valid[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = it + u * STEP + wave * KPW + grp;
       valid[u] = j < k1;
       const size_t row = (size_t)(valid[u] ? j : k1 - 1) * D;   // rows past the chunk re-read its last row
-      load8(Kh + row, kx[u]);
-      load8(Vh + row, vx[u]);
+      st.load_row(Kh + row, Vh + row, u);
     }
     float s[U][G];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dot = fmaf(qf[h][e], kx[u][e], dot);
-        dot = row_sum<LPR>(dot);
+        const float dot = st.finish_score(row_sum<LPR>(st.partial_score(h, u)), a.scale_log2e);
         s[u][h] = valid[u] ? dot : -INFINITY;
       }
     }
@@ -142,21 +222,12 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
 #pragma unroll
       for (int u = 0; u < U; ++u) mn = fmaxf(mn, s[u][h]);
       const float corr = exp2_rel(m[h], mn);
-      float p[U], psum = 0.f;
+      float p[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        p[u] = exp2_rel(s[u][h], mn);
-        psum += p[u];
-      }
+      for (int u = 0; u < U; ++u) p[u] = exp2_rel(s[u][h], mn);
+      const float psum = st.accumulate(acc[h], corr, p);
       l[h] = fmaf(l[h], corr, psum);
       m[h] = mn;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = acc[h][e] * corr;
-#pragma unroll
-        for (int u = 0; u < U; ++u) v = fmaf(p[u], vx[u][e], v);
-        acc[h][e] = v;
-      }
     }
   }
 
@@ -254,7 +325,7 @@ int heads_per_workgroup(int g) { return g % 8 == 0 ? 8 : (g % 4 == 0 ? 4 : (g % 
 // Rows per chunk, fixed by the capacity n so that the workspace bound holds for every len <= n.
 int chunk_rows(int B, int Hkv, int g, int n) {
   const long long groups = (long long)B * Hkv * (g / heads_per_workgroup(g));
-  int chunk = 1024;
+  int chunk = DECODE_CHUNK;
   while (chunk > 64 && ((long long)(n + chunk - 1) / chunk) * groups < DECODE_TARGET_WGS) chunk >>= 1;
   return chunk;
 }
