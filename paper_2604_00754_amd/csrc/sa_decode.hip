@@ -281,26 +281,33 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
   }
 }
 
-// One workgroup per (b, hq): merges the partial results of the chunks.
+// One workgroup per (b, hq): merges the partial results of the chunks.  The rows of the partial results are
+// spread over 16 waves, so that even a cache cut into hundreds of chunks costs a few dependent steps.
+constexpr int kMergeWaves = 16;
+
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void decode_merge_kernel(const float* __restrict__ part, T* __restrict__ Y,
-                                                                float* __restrict__ LSE, int splits) {
+__global__ __launch_bounds__(kMergeWaves * 64) void decode_merge_kernel(const float* __restrict__ part,
+                                                                        T* __restrict__ Y, float* __restrict__ LSE,
+                                                                        int splits) {
   constexpr int EPL = (D + 63) / 64;   // elements per lane
-  __shared__ float lds_m[kWaves];
-  __shared__ float lds_acc[kWaves][D + 1];
+  __shared__ float lds_m[kMergeWaves];
+  __shared__ float lds_acc[kMergeWaves][D + 1];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* P = part + (size_t)blockIdx.x * splits * (D + 2);
 
   float M = -INFINITY;
-  for (int s = threadIdx.x; s < splits; s += kThreads) M = fmaxf(M, P[(size_t)s * (D + 2) + D]);
+  for (int s = threadIdx.x; s < splits; s += kMergeWaves * 64) M = fmaxf(M, P[(size_t)s * (D + 2) + D]);
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off));
   if (lane == 0) lds_m[wave] = M;
   __syncthreads();
-  M = fmaxf(fmaxf(lds_m[0], lds_m[1]), fmaxf(lds_m[2], lds_m[3]));
+  M = lds_m[0];
+#pragma unroll
+  for (int w = 1; w < kMergeWaves; ++w) M = fmaxf(M, lds_m[w]);
 
   float acc[EPL] = {}, L = 0.f;
-  for (int s = wave; s < splits; s += kWaves) {
+#pragma unroll 4   // independent rows: keep several loads in flight
+  for (int s = wave; s < splits; s += kMergeWaves) {
     const float* row = P + (size_t)s * (D + 2);
     const float c = exp2f(row[D] - M);
     L = fmaf(c, row[D + 1], L);
@@ -313,8 +320,12 @@ __global__ __launch_bounds__(kThreads) void decode_merge_kernel(const float* __r
   __syncthreads();
   if (threadIdx.x < D) {
     const int e = threadIdx.x;
-    const float Lt = lds_acc[0][D] + lds_acc[1][D] + lds_acc[2][D] + lds_acc[3][D];
-    const float v = lds_acc[0][e] + lds_acc[1][e] + lds_acc[2][e] + lds_acc[3][e];
+    float Lt = 0.f, v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kMergeWaves; ++w) {
+      Lt += lds_acc[w][D];
+      v += lds_acc[w][e];
+    }
     store1(Y + (size_t)blockIdx.x * D + e, v / Lt);
     if (e == 0 && LSE) LSE[blockIdx.x] = (M + log2f(Lt)) * kLn2;
   }
@@ -337,7 +348,7 @@ hipError_t launch_typed(const Decode& d, const Args& a, hipStream_t st) {
   decode_partial_kernel<T, D, G><<<grid, kThreads, 0, st>>>(a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  decode_merge_kernel<T, D><<<d.B * d.Hq, kThreads, 0, st>>>(a.part, reinterpret_cast<T*>(d.Y), d.LSE, a.splits);
+  decode_merge_kernel<T, D><<<d.B * d.Hq, kMergeWaves * 64, 0, st>>>(a.part, reinterpret_cast<T*>(d.Y), d.LSE, a.splits);
   return hipGetLastError();
 }
 
