@@ -20,6 +20,15 @@
 #ifndef DECODE_TARGET_WGS
 #define DECODE_TARGET_WGS 512    // ... shortened (down to 64 rows) until the launch has at least this many workgroups
 #endif
+#ifndef DECODE_TRANSPOSED
+#define DECODE_TRANSPOSED 1
+#endif
+#ifndef DECODE_TRANSPOSED_MIN_G
+#define DECODE_TRANSPOSED_MIN_G 4
+#endif
+#ifndef DECODE_WAVES_PER_SIMD
+#define DECODE_WAVES_PER_SIMD(T, D, G) ((sizeof(T) == 2 && (D) == 128 && (G) >= 8) ? 3 : 1)   // register budget asked of the compiler (512 / waves)
+#endif
 #ifndef DECODE_UNROLL
 #define DECODE_UNROLL 4          // wave-wide K (and V) loads in flight per loop iteration
 #endif
@@ -43,6 +52,35 @@ __device__ __forceinline__ float row_sum(float v) {
   v += dpp_move<0x141>(v);   // row_half_mirror: lane i <-> 7 - i of each 8
   if (LPR == 16) v += dpp_move<0x140>(v);  // row_mirror: lane i <-> 15 - i
   return v;
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
+// Halving steps of a transposed sum over a row of 16 lanes (4 banks of 4).  The result is x + x(partner) in
+// the lanes of one half of the banks and y + y(partner) in the other half: each lane gives one of its two values
+// away and keeps the other, so two values cost two instructions instead of four.  A DPP instruction must not
+// read a register in the two issue slots after a vector instruction wrote it, and the compiler does not look
+// inside the block: hence the waits at both ends.
+__device__ __forceinline__ float add_split_mirror(float x, float y) {        // partner 15 - i; banks {0,1} | {2,3}
+  float r;
+  asm("s_nop 1\n\t"
+      "v_add_f32_dpp %0, %1, %1 row_mirror row_mask:0xf bank_mask:0x3\n\t"
+      "v_add_f32_dpp %0, %2, %2 row_mirror row_mask:0xf bank_mask:0xc\n\t"
+      "s_nop 1"
+      : "=&v"(r) : "v"(x), "v"(y));
+  return r;
+}
+__device__ __forceinline__ float add_split_half_mirror(float x, float y) {   // partner 7 - i of each 8; banks {0,2} | {1,3}
+  float r;
+  asm("s_nop 1\n\t"
+      "v_add_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0x5\n\t"
+      "v_add_f32_dpp %0, %2, %2 row_half_mirror row_mask:0xf bank_mask:0xa\n\t"
+      "s_nop 1"
+      : "=&v"(r) : "v"(x), "v"(y));
+  return r;
 }
 
 __device__ __forceinline__ void load8(const bf16_t* p, float (&out)[8]) {
@@ -144,33 +182,43 @@ struct Lane<bf16_t, G, U> {
     return dot;
   }
   static __device__ __forceinline__ float finish_score(float dot, float scale_log2e) { return dot * scale_log2e; }
-  __device__ __forceinline__ float accumulate(float (&acc)[8], float corr, const float (&p)[U]) const {
-    float psum = 0.f;
+  // acc = acc * corr + sum_u w[u] * V_u with the weights as bf16 pairs pp[u/2] = (w[u], w[u+1])
+  __device__ __forceinline__ void accumulate_packed(float (&acc)[8], float corr, const uint32_t (&pp)[U / 2]) const {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] *= corr;
 #pragma unroll
     for (int u = 0; u < U; u += 2) {
-      const uint32_t pp = pack_bf16(p[u], p[u + 1]);
-      psum += bf16lo(pp) + bf16hi(pp);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         // (V_u[2i], V_u+1[2i]) and (V_u[2i+1], V_u+1[2i+1])
         const uint32_t even = __builtin_amdgcn_perm(vx[u + 1][i], vx[u][i], 0x05040100u);
         const uint32_t odd = __builtin_amdgcn_perm(vx[u + 1][i], vx[u][i], 0x07060302u);
-        acc[2 * i] = dot2(even, pp, acc[2 * i]);
-        acc[2 * i + 1] = dot2(odd, pp, acc[2 * i + 1]);
+        acc[2 * i] = dot2(even, pp[u / 2], acc[2 * i]);
+        acc[2 * i + 1] = dot2(odd, pp[u / 2], acc[2 * i + 1]);
       }
     }
+  }
+  __device__ __forceinline__ float accumulate(float (&acc)[8], float corr, const float (&p)[U]) const {
+    float psum = 0.f;
+    uint32_t pp[U / 2];
+#pragma unroll
+    for (int u = 0; u < U; u += 2) {
+      pp[u / 2] = pack_bf16(p[u], p[u + 1]);
+      psum += bf16lo(pp[u / 2]) + bf16hi(pp[u / 2]);
+    }
+    accumulate_packed(acc, corr, pp);
     return psum;
   }
 };
 
 template <typename T, int D, int G>
-__global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
+__global__ __launch_bounds__(kThreads, DECODE_WAVES_PER_SIMD(T, D, G)) void decode_partial_kernel(Args a) {
   constexpr int LPR = D / 8;          // lanes per row
   constexpr int KPW = 64 / LPR;       // rows per wave-wide load
   constexpr int STEP = kWaves * KPW;  // rows per workgroup per load
   constexpr int U = DECODE_UNROLL;
+  // bf16 rows over 16 lanes, four loads per iteration: one load per bank of a DPP row
+  constexpr bool kTransposed = DECODE_TRANSPOSED && sizeof(T) == 2 && LPR == 16 && U == 4 && G >= DECODE_TRANSPOSED_MIN_G;
   __shared__ float lds_acc[kWaves][G][D];
   __shared__ float lds_ml[kWaves][G][2];
 
@@ -207,6 +255,35 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
       const size_t row = (size_t)(valid[u] ? j : k1 - 1) * D;   // rows past the chunk re-read its last row
       st.load_row(Kh + row, Vh + row, u);
     }
+    if constexpr (kTransposed) {
+      // Bank b of a row of 16 lanes ends up with the scores of load u = b only (all G heads), computes their
+      // weights once instead of in all 16 lanes, and the four banks exchange the weights as bf16 pairs.
+      const int bank = (lane >> 2) & 3;
+      const bool own_valid = it + bank * STEP + wave * KPW + grp < k1;
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float r0 = add_split_mirror(st.partial_score(h, 0), st.partial_score(h, 2));   // banks 0,1: u = 0 | banks 2,3: u = 2
+        const float r1 = add_split_mirror(st.partial_score(h, 1), st.partial_score(h, 3));   //            u = 1 |            u = 3
+        float t = add_split_half_mirror(r0, r1);                                             // bank b: u = b
+        t += dpp_move<0xB1>(t);
+        t += dpp_move<0x4E>(t);
+        const float own = own_valid ? t * a.scale_log2e : -INFINITY;
+        float mn = fmaxf(own, dpp_move<0x140>(own));
+        mn = fmaxf(mn, dpp_move<0x141>(mn));
+        mn = fmaxf(mn, m[h]);
+        const float corr = exp2_rel(m[h], mn);
+        const float w = exp2_rel(own, mn);
+        m[h] = mn;
+        // (own, neighbour bank's) -> (even bank's, odd bank's); then the other pair from the mirrored bank
+        uint32_t pair = pack_bf16(w, dpp_move<0x141>(w));
+        l[h] = fmaf(l[h], corr, bf16lo(pair));             // this bank's share; the banks are summed after the loop
+        pair = __builtin_amdgcn_alignbit(pair, pair, (bank & 1) ? 16u : 0u);
+        const uint32_t other = dpp_move_u32<0x140>(pair);
+        const uint32_t pp[2] = {bank < 2 ? pair : other, bank < 2 ? other : pair};
+        st.accumulate_packed(acc[h], corr, pp);
+      }
+      continue;
+    }
     float s[U][G];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -231,6 +308,13 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(Args a) {
     }
   }
 
+  if constexpr (kTransposed) {   // every bank of a row kept its own share of the sums
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      l[h] += dpp_move<0x140>(l[h]);
+      l[h] += dpp_move<0x141>(l[h]);
+    }
+  }
   // merge the KPW lane groups of the wave (same `sub`, different rows)
 #pragma unroll
   for (int h = 0; h < G; ++h) {
