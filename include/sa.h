@@ -199,6 +199,13 @@ sa_status sa_dual_path_bwd(const sa_desc* sa, const sa_desc* swa, const void* Q,
 sa_status sa_decode_fwd(const sa_desc* desc, const void* q, const void* K, const void* V, int32_t len, void* Y,
                         float* LSE, void* ws, size_t ws_bytes, void* stream);
 
+/* sa_decode_fwd for a batch whose sequences have different numbers of cached rows: lens [B] (int32, device
+ * memory) gives the rows of each sequence, max_len (host, 1 <= max_len <= n) an upper bound of them that sizes the
+ * launch.  The values of lens cannot be checked on the host: each is clamped to 1..max_len on the device. */
+sa_status sa_decode_fwd_varlen(const sa_desc* desc, const void* q, const void* K, const void* V,
+                               const int32_t* lens, int32_t max_len, void* Y, float* LSE, void* ws,
+                               size_t ws_bytes, void* stream);
+
 /* Eq. 1: windowed attention in the original order (sa_fwd with the identity permutation). */
 sa_status swa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                   void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);

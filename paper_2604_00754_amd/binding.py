@@ -21,7 +21,7 @@ SA_OP_DECODE = 9
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
            "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
-           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd")
+           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd", "sa_decode_fwd_varlen")
 
 
 class sa_desc(C.Structure):
@@ -73,6 +73,8 @@ def _load():
     lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.sa_decode_fwd.restype = C.c_int
     lib.sa_decode_fwd.argtypes = [dp, vp, vp, vp, C.c_int32, vp, vp, vp, sz, vp]
+    lib.sa_decode_fwd_varlen.restype = C.c_int
+    lib.sa_decode_fwd_varlen.argtypes = [dp, vp, vp, vp, ip, C.c_int32, vp, vp, vp, sz, vp]
     lib.swa_fwd.restype = C.c_int
     lib.swa_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gated_sa_swa_fwd.restype = C.c_int
@@ -182,6 +184,12 @@ def sa_decode_fwd(desc, q, K, V, length, Y, LSE, ws):
     _check(_lib.sa_decode_fwd(C.byref(desc), _ptr(q), _ptr(K), _ptr(V), int(length), _ptr(Y), _ptr(LSE), _ptr(ws),
                               (ws.numel() * ws.element_size()) if ws is not None else 0, _stream()),
            "sa_decode_fwd")
+
+
+def sa_decode_fwd_varlen(desc, q, K, V, lens, max_len, Y, LSE, ws):
+    _check(_lib.sa_decode_fwd_varlen(C.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(lens), int(max_len), _ptr(Y),
+                                     _ptr(LSE), _ptr(ws), (ws.numel() * ws.element_size()) if ws is not None else 0,
+                                     _stream()), "sa_decode_fwd_varlen")
 
 
 def swa_fwd(desc, Q, K, V, Y, LSE=None):

@@ -192,8 +192,25 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   return hip_status(run_fwd(c, p, (hipStream_t)stream));
 }
 
+namespace {
+sa_status decode_common(const sa_desc* c, const void* q, const void* K, const void* V, const int32_t* lens,
+                        int32_t len, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
+}
+
 sa_status sa_decode_fwd(const sa_desc* c, const void* q, const void* K, const void* V, int32_t len, void* Y,
                         float* LSE, void* ws, size_t ws_bytes, void* stream) {
+  return decode_common(c, q, K, V, nullptr, len, Y, LSE, ws, ws_bytes, stream);
+}
+
+sa_status sa_decode_fwd_varlen(const sa_desc* c, const void* q, const void* K, const void* V, const int32_t* lens,
+                               int32_t max_len, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream) {
+  if (!lens) return SA_ERR_NULL;
+  return decode_common(c, q, K, V, lens, max_len, Y, LSE, ws, ws_bytes, stream);
+}
+
+namespace {
+sa_status decode_common(const sa_desc* c, const void* q, const void* K, const void* V, const int32_t* lens,
+                        int32_t len, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream) {
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!q || !K || !V || !Y) return SA_ERR_NULL;
@@ -206,8 +223,10 @@ sa_status sa_decode_fwd(const sa_desc* c, const void* q, const void* K, const vo
   d.B = c->B; d.Hq = c->Hq; d.Hkv = c->Hkv; d.n = c->n; d.d = c->d; d.len = len;
   d.bf16 = c->dtype == SA_BF16;
   d.scale = c->scale > 0.f ? c->scale : 1.0f / sqrtf((float)c->d);
+  d.lens = lens;
   return hip_status(sa::launch_decode(d, (hipStream_t)stream));
 }
+}  // namespace
 
 sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t* perm, void* ws, size_t ws_bytes,
                          void* stream) {

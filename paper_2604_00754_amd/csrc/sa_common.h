@@ -89,6 +89,7 @@ struct Decode {
   void* Y;         // [B,Hq,d]
   float* LSE;      // [B,Hq], may be nullptr
   float* part;     // decode_workspace_bytes(...) bytes
+  const int32_t* lens;   // [B] device, or nullptr: every sequence has `len` rows; else len = the largest
   int B, Hq, Hkv, n, d, len, bf16;
   float scale;
 };

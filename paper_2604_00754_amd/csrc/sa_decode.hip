@@ -112,6 +112,7 @@ struct Args {
   const void* K;
   const void* V;
   float* part;      // [B*Hq][splits][d + 2]: weighted V sum, then running max (log2 domain) and sum
+  const int32_t* lens;   // per-sequence row counts [B] or nullptr (then every sequence has `len` rows)
   int Hq, Hkv, g, n, len, chunk, splits;
   float scale_log2e;
 };
@@ -245,7 +246,16 @@ __global__ __launch_bounds__(kThreads, DECODE_WAVES_PER_SIMD(T, D, G)) void deco
   }
 
   const int k0 = split * a.chunk;
-  const int k1 = min(a.len, k0 + a.chunk);   // k0 < k1 <= len by the launch geometry
+  // the launch covers `len` rows; a sequence with fewer rows (clamped to 1..len) leaves its last chunks empty
+  const int len_b = a.lens ? min(max(a.lens[b], 1), a.len) : a.len;
+  const int k1 = min(len_b, k0 + a.chunk);
+  if (k0 >= k1) {   // uniform over the workgroup: an empty chunk contributes weight zero to the merge
+    for (int idx = threadIdx.x; idx < G * (D + 2); idx += kThreads) {
+      const int h = idx / (D + 2), e = idx % (D + 2);
+      a.part[(((size_t)b * a.Hq + hq0 + h) * a.splits + split) * (D + 2) + e] = e == D ? -INFINITY : 0.f;
+    }
+    return;
+  }
   for (int it = k0; it < k1; it += STEP * U) {
     bool valid[U];
 #pragma unroll
@@ -459,6 +469,7 @@ hipError_t launch_decode(const Decode& d, hipStream_t st) {
   Args a;
   a.q = d.q; a.K = d.K; a.V = d.V;
   a.part = d.part;
+  a.lens = d.lens;
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.g = d.Hq / d.Hkv; a.n = d.n; a.len = d.len;
   a.chunk = chunk_rows(d.B, d.Hkv, a.g, d.n);
   a.splits = (d.len + a.chunk - 1) / a.chunk;

@@ -138,6 +138,10 @@ def test_decode_step_arguments():
     assert call(ws=None) == sa.SA_ERR_WORKSPACE
     assert call(ws_bytes=need - 1) == sa.SA_ERR_WORKSPACE
     assert lib.sa_decode_fwd(None, FAKE, FAKE, FAKE, 1, FAKE, None, FAKE, need, None) == sa.SA_ERR_NULL
+    # the per-sequence form takes the same checks, and needs its length array
+    assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, None, 1000, FAKE, None, FAKE, need, None) == sa.SA_ERR_NULL
+    assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, FAKE, 1001, FAKE, None, FAKE, need, None) == sa.SA_ERR_SHAPE
+    assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, FAKE, 1000, FAKE, None, FAKE, need - 1, None) == sa.SA_ERR_WORKSPACE
     # the workspace is sized by the capacity: it never grows when the descriptor's n shrinks
     small = sa.make_desc(2, 8, 2, 500, 128, 256)
     assert sa.sa_workspace_bytes(small, sa.SA_OP_DECODE) <= need

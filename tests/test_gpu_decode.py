@@ -92,6 +92,49 @@ def test_decode_continues_the_prompt_pass():
         assert (L - Lp[:, :, length - 1]).abs().max().item() <= 1e-3
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,n,d,lens", [
+    (4, 8, 2, 1500, 128, [1500, 1, 700, 513]),
+    (3, 8, 1, 900, 64, [64, 65, 900]),
+    (5, 4, 4, 2100, 128, [2100, 2099, 33, 1024, 1025]),
+    (2, 6, 2, 800, 128, [5, 300]),          # max_len below the capacity
+])
+def test_sequences_of_different_lengths(B, Hq, Hkv, n, d, lens):
+    """sa_decode_fwd_varlen: every sequence of the batch against the oracle run on that sequence alone with its own
+    length; rows beyond a sequence's length are NaN."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    print(f"case decode varlen B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} lens{lens}", flush=True)
+    wl, x = U.make_case(B, Hq, Hkv, n, d, 2, "bf16", seed=7, identity=True)
+    q = U.to_dev(np.ascontiguousarray(x["Q"][:, :, 0]), "bf16")
+    K, V = U.to_dev(x["K"], "bf16"), U.to_dev(x["V"], "bf16")
+    q64, k64, v64 = U.to_np64(q), U.to_np64(K), U.to_np64(V)
+    for b, ln in enumerate(lens):
+        K[b, :, ln:] = float("nan")
+        V[b, :, ln:] = float("nan")
+    desc = sa.make_desc(B, Hq, Hkv, n, d, 2)
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_DECODE), dtype=torch.uint8, device=U.DEV)
+    ws.fill_(255)   # NaN patterns: every partial result the merge reads must have been written
+    Y = torch.full((B, Hq, d), float("nan"), device=U.DEV, dtype=torch.bfloat16)
+    L = torch.full((B, Hq), float("nan"), device=U.DEV, dtype=torch.float32)
+    lens_dev = torch.tensor(lens, device=U.DEV, dtype=torch.int32)
+    sa.sa_decode_fwd_varlen(desc, q, K, V, lens_dev, max(lens), Y, L, ws)
+    torch.cuda.synchronize()
+    for b, ln in enumerate(lens):
+        Yr, Lr = orc.decode_fwd(orc.desc(1, Hq, Hkv, n, d, 2), q64[b:b + 1], k64[b:b + 1], v64[b:b + 1], ln)
+        U.assert_close(U.to_np64(Y[b:b + 1]), Yr, "bf16", f"decode Y, sequence {b}")
+        assert np.abs(L[b:b + 1].cpu().numpy().astype(np.float64) - Lr).max() <= 1e-3
+    # out-of-range entries are clamped to 1..max_len instead of reading outside the cache
+    bad = torch.tensor([0] + [10 ** 9] * (B - 1), device=U.DEV, dtype=torch.int32)
+    K2, V2 = U.to_dev(x["K"], "bf16"), U.to_dev(x["V"], "bf16")
+    Y2 = torch.empty_like(Y)
+    sa.sa_decode_fwd_varlen(desc, q, K2, V2, bad, max(lens), Y2, None, ws)
+    torch.cuda.synchronize()
+    Yr, _ = orc.decode_fwd(orc.desc(1, Hq, Hkv, n, d, 2), q64[:1], k64[:1], v64[:1], 1)
+    U.assert_close(U.to_np64(Y2[:1]), Yr, "bf16", "clamped to one row")
+    Yr, _ = orc.decode_fwd(orc.desc(1, Hq, Hkv, n, d, 2), q64[1:2], k64[1:2], v64[1:2], max(lens))
+    U.assert_close(U.to_np64(Y2[1:2]), Yr, "bf16", "clamped to max_len")
+
+
 @pytest.mark.parametrize("Hq,Hkv,n,length", [(32, 8, 32768, 32768), (32, 8, 32768, 30001), (32, 4, 131072, 131072)])
 def test_full_size_caches(Hq, Hkv, n, length):
     """The cache of the headline prefill shape (Qwen3-8B heads, 32K rows) and of the long one (32/4 heads, 128K
