@@ -261,11 +261,20 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(Prep p) {
 
   // gated: dO_x = sig(gamma_x) * dY;  D_x = sum_d dO_x * Y_x;  dgamma_x = sig'(gamma_x) * dY * Y_x
   float ga[E], gb[E];
+  if (p.gate_per_dim) {
 #pragma unroll
-  for (int k = 0; k < E; ++k) {
-    const size_t gi = p.gate_per_dim ? off + k : r;
-    ga[k] = sigmoidf_exact(load_gate(p.gate_a, gi, p.gate_f32));
-    gb[k] = sigmoidf_exact(load_gate(p.gate_b, gi, p.gate_f32));
+    for (int k = 0; k < E; ++k) {
+      ga[k] = sigmoidf_exact(load_gate(p.gate_a, off + k, p.gate_f32));
+      gb[k] = sigmoidf_exact(load_gate(p.gate_b, off + k, p.gate_f32));
+    }
+  } else {  // one gate per row: one sigmoid, not one per element
+    const float a1 = sigmoidf_exact(load_gate(p.gate_a, r, p.gate_f32));
+    const float b1 = sigmoidf_exact(load_gate(p.gate_b, r, p.gate_f32));
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+      ga[k] = a1;
+      gb[k] = b1;
+    }
   }
   float da[E], db[E], sa = 0.f, sb = 0.f, ra = 0.f, rb = 0.f;
 #pragma unroll
