@@ -142,6 +142,9 @@ def test_decode_step_arguments():
     assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, None, 1000, FAKE, None, FAKE, need, None) == sa.SA_ERR_NULL
     assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, FAKE, 1001, FAKE, None, FAKE, need, None) == sa.SA_ERR_SHAPE
     assert lib.sa_decode_fwd_varlen(C.byref(d), FAKE, FAKE, FAKE, FAKE, 1000, FAKE, None, FAKE, need - 1, None) == sa.SA_ERR_WORKSPACE
+    # more (b, hq) pairs than one launch dimension holds
+    wide = sa.make_desc(2048, 64, 64, 16, 64, 2)
+    assert lib.sa_decode_fwd(C.byref(wide), FAKE, FAKE, FAKE, 16, FAKE, None, FAKE, 1 << 40, None) == sa.SA_ERR_UNSUPPORTED
     # the workspace is sized by the capacity: it never grows when the descriptor's n shrinks
     small = sa.make_desc(2, 8, 2, 500, 128, 256)
     assert sa.sa_workspace_bytes(small, sa.SA_OP_DECODE) <= need

@@ -60,6 +60,17 @@ def test_cache_lengths_around_load_and_chunk_edges(d):
         run_decode(1, 4, 1, 300, d, length, seed=length)
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,n,d,length", [
+    (1, 4, 4, 1, 64, 1),          # a cache of one row
+    (1, 8, 2, 65, 128, 65),       # second chunk holds a single row
+    (2, 8, 8, 64, 128, 64),       # exactly one chunk
+    (1, 32, 8, 2048, 128, 1025),  # chunks of 64 rows (few KV heads): 17 chunks, the last one ragged
+    (64, 8, 8, 1024, 64, 1000),   # many sequences: chunks of 512 rows
+])
+def test_chunk_geometry_corner_cases(B, Hq, Hkv, n, d, length):
+    run_decode(B, Hq, Hkv, n, d, length)
+
+
 def test_softmax_scale_and_single_cached_row():
     from paper_2604_00754_amd import binding as sa
     run_decode(1, 8, 2, 257, 128, 200, scale=0.31)
