@@ -147,6 +147,8 @@ def training_ops(sa, synth, dev, reps):
     dWsa, dWswa = torch.empty_like(Wsa), torch.empty_like(Wswa)
     wsg = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATE_PROJ_BWD), device=dev, dtype=torch.uint8)
     _, t_gp = time_side(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
+    # inference form: the gate values are not kept (two of the three output tensors are not written)
+    _, t_gpi = time_side(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, None, None), reps, 2)
     _, t_gpb = time_side(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
                                                    dWsa, dWswa, wsg), reps, 2)
     # the whole layer of Alg. 2 in one call each way (both branches + gate projections)
@@ -162,6 +164,8 @@ def training_ops(sa, synth, dev, reps):
     return {"pretrain_8k": {
         "gate_proj_fwd_ms": t_gp, "gate_proj_fwd_tflops": flop_gp / (t_gp * 1e-3) / 1e12,
         "gate_proj_fwd_frac_mfma_peak": flop_gp / (t_gp * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "gate_proj_fwd_no_gate_outputs_ms": t_gpi,
+        "gate_proj_fwd_no_gate_outputs_tflops": flop_gp / (t_gpi * 1e-3) / 1e12,
         "gate_proj_bwd_ms": t_gpb, "gate_proj_bwd_tflops": 2 * flop_gp / (t_gpb * 1e-3) / 1e12,
         "shape": "B4 H16 n8192 d64 w256 bf16",
         "sa_fwd_ms": t_fwd, "sa_bwd_ms": t_bwd,
