@@ -738,3 +738,55 @@ def test_decode_step_against_sdpa_the_prefill_row_and_closed_forms():
     for bad in (0, n + 1):
         with pytest.raises(ValueError):
             orc.decode_fwd(c, q, K, V, bad)
+
+
+def test_decode_step_ignores_the_order_of_cached_rows():
+    """Softmax attention over a set of rows does not depend on their order: moving K and V rows together (any
+    relabelling of cache positions, as a paged or permuted cache would do) leaves Y and LSE unchanged."""
+    B, Hq, Hkv, n, d, length = 1, 4, 2, 40, 8, 31
+    c = orc.desc(B, Hq, Hkv, n, d, 1)
+    q, K, V = rnd((B, Hq, d), 611), rnd((B, Hkv, n, d), 612), rnd((B, Hkv, n, d), 613)
+    Y, L = orc.decode_fwd(c, q, K, V, length)
+    order = np.random.default_rng(614).permutation(length)
+    K2, V2 = K.copy(), V.copy()
+    K2[:, :, :length], V2[:, :, :length] = K[:, :, order], V[:, :, order]
+    Y2, L2 = orc.decode_fwd(c, q, K2, V2, length)
+    np.testing.assert_allclose(Y2, Y, atol=1e-13)
+    np.testing.assert_allclose(L2, L, atol=1e-13)
+    # and a row appended to the cache enters with weight e^{z - LSE'}: LSE' = log(e^{LSE} + e^{z_new})
+    Y3, L3 = orc.decode_fwd(c, q, K, V, length + 1)
+    g = Hq // Hkv
+    z_new = np.einsum("bhd,bhd->bh", q, np.repeat(K[:, :, length], g, axis=1)) / math.sqrt(d)
+    np.testing.assert_allclose(L3, np.logaddexp(L, z_new), atol=1e-12)
+    w_new = np.exp(z_new - L3)[..., None]
+    np.testing.assert_allclose(Y3, (1 - w_new) * Y + w_new * np.repeat(V[:, :, length], g, axis=1), atol=1e-12)
+
+
+def test_random_small_cases_alg1_form_equals_dense_mask_form():
+    """Seeded sweep over small random shapes (sizes, GQA ratios, windows around and above n, every window kind,
+    shared and per-head permutations): the oracle's Alg. 1 form against the dense-mask form of Eq. 4."""
+    g = np.random.default_rng(20260400754)
+    for case in range(40):
+        Hkv = int(g.integers(1, 3))
+        Hq = Hkv * int(g.integers(1, 4))
+        B = int(g.integers(1, 3))
+        n = int(g.integers(1, 34))
+        d = int(g.choice([1, 3, 8]))
+        w = int(g.integers(1, 2 * n + 3))
+        window = int(g.choice(KINDS))
+        causal = int(g.integers(0, 2))
+        pb, ph = int(g.choice([1, B])), int(g.choice([1, Hq]))
+        c = orc.desc(B, Hq, Hkv, n, d, w, window, causal, perm_B=pb, perm_H=ph)
+        Q, K, V = rnd((B, Hq, n, d), 700 + case), rnd((B, Hkv, n, d), 800 + case), rnd((B, Hkv, n, d), 900 + case)
+        perm = rand_perm(pb, ph, n, 1000 + case)
+        Y, L = orc.sa_fwd(c, Q, K, V, perm)
+        Yd = np.empty_like(Y)
+        Ld = np.empty_like(L)
+        scale = 1.0 / math.sqrt(d)
+        for b in range(B):
+            for h in range(Hq):
+                p = perm[0 if pb == 1 else b, 0 if ph == 1 else h]
+                mask = dense_mask(n, w, window, causal, inverse(p))
+                Yd[b, h], Ld[b, h] = dense_attention(Q[b, h], K[b, h // (Hq // Hkv)], V[b, h // (Hq // Hkv)], mask, scale)
+        np.testing.assert_allclose(Y, Yd, atol=1e-11, err_msg=f"case {case}: {(B, Hq, Hkv, n, d, w, window, causal, pb, ph)}")
+        np.testing.assert_allclose(L, Ld, atol=1e-11)
