@@ -17,7 +17,9 @@
  * Conventions
  *   - All tensor pointers are DEVICE pointers owned by the caller, contiguous row-major, 16-byte
  *     aligned: Q, Y, dY, dQ, Y_sa, Y_swa [B,Hq,n,d]; K, V, dK, dV [B,Hkv,n,d]; LSE [B,Hq,n] float.
- *     Query head hq uses kv head hq / (Hq/Hkv).
+ *     Query head hq uses kv head hq / (Hq/Hkv).  Alignment is checked on the host: a tensor, weight or
+ *     workspace pointer that is not 16-byte aligned, or an index / LSE / gate array not aligned to its
+ *     element, gives SA_ERR_UNSUPPORTED before anything is launched.
  *   - perm: int32 [perm_B, perm_H, n]; perm[..., p] is the ORIGINAL index of the token placed at
  *     permuted slot p (the index tensor of "Q[sigma]" in Sec. 3.3; it is the inverse of the map
  *     sigma(i) = slot of token i used in Eq. 3).  perm_B in {1,B}, perm_H in {1,Hq}.  NULL means the

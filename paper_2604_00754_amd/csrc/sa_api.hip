@@ -2,6 +2,8 @@
 // Validation happens here, before any launch; kernels live in the other files of this directory.
 #include <math.h>
 
+#include <initializer_list>
+
 #include "sa_common.h"
 
 namespace {
@@ -73,6 +75,17 @@ bool same_problem(const sa_desc* a, const sa_desc* b) {
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Tensors are read and written with 16-byte vector accesses (and copied into LDS 16 bytes at a time); index,
+// LSE and gate arrays with their element size.  Null pointers pass: they are optional arguments here.
+// gate logits: per-dimension tensors are read like the other tensors, per-row ones element by element
+size_t gate_alignment(const sa_desc* c) { return c->gate_per_dim ? 16 : (c->gate_dtype == SA_F32 ? 4 : 2); }
+
+bool aligned_to(size_t a, std::initializer_list<const void*> ptrs) {
+  for (const void* q : ptrs)
+    if (q && (reinterpret_cast<uintptr_t>(q) & (a - 1))) return false;
+  return true;
+}
 
 struct BwdWorkspace {
   size_t off_Da, off_Db, off_dOa, off_dOb, total;
@@ -166,6 +179,7 @@ sa_status sa_check_perm(const sa_desc* c, const int32_t* perm, void* ws, size_t 
   if (s != SA_OK) return s;
   if (!perm) return SA_ERR_NULL;
   const size_t need = sa_workspace_bytes(c, SA_OP_CHECK_PERM);
+  if (!aligned_to(4, {perm, ws})) return SA_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < need) return SA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   int* seen = reinterpret_cast<int*>(ws);
@@ -186,6 +200,7 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!Q || !K || !V || !Y) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, Y}) || !aligned_to(4, {perm, LSE})) return SA_ERR_UNSUPPORTED;
   Pass p = make_pass(c, Q, K, V, perm);
   p.Y = Y;
   p.LSE = LSE;
@@ -215,6 +230,7 @@ sa_status decode_common(const sa_desc* c, const void* q, const void* K, const vo
   if (s != SA_OK) return s;
   if (!q || !K || !V || !Y) return SA_ERR_NULL;
   if (len < 1 || len > c->n) return SA_ERR_SHAPE;
+  if (!aligned_to(16, {q, K, V, Y, ws}) || !aligned_to(4, {lens, LSE})) return SA_ERR_UNSUPPORTED;
   if ((long long)c->B * c->Hq > 65535) return SA_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < sa_workspace_bytes(c, SA_OP_DECODE)) return SA_ERR_WORKSPACE;
   sa::Decode d = {};
@@ -234,6 +250,7 @@ sa_status sa_sample_perm(const sa_desc* c, uint64_t seed, int32_t layer, int32_t
   if (s != SA_OK) return s;
   if (!perm) return SA_ERR_NULL;
   if (layer < 0) return SA_ERR_SHAPE;
+  if (!aligned_to(4, {perm})) return SA_ERR_UNSUPPORTED;
   if (c->n > (1 << 20)) return SA_ERR_UNSUPPORTED;
   const int slices = c->perm_B * c->perm_H;
   if (ws && ws_bytes < sa::sample_perm_workspace_bytes(slices, c->n)) return SA_ERR_WORKSPACE;
@@ -245,6 +262,8 @@ sa_status sa_fwd_rope(const sa_desc* c, const void* Q, const void* K, const void
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!Q || !K || !V || !Y || !rope_table) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, Y}) || !aligned_to(4, {perm, LSE})) return SA_ERR_UNSUPPORTED;
+  if (!aligned_to(8, {rope_table})) return SA_ERR_UNSUPPORTED;
   if (!(interleaved == 0 || interleaved == 1)) return SA_ERR_SHAPE;
   if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
   Pass p = make_pass(c, Q, K, V, perm);
@@ -257,6 +276,7 @@ sa_status sa_fwd_rope(const sa_desc* c, const void* Q, const void* K, const void
 
 sa_status sa_rope_table(int32_t n, int32_t d, double base, int32_t pos0, float* table, void* stream) {
   if (!table) return SA_ERR_NULL;
+  if (!aligned_to(8, {table})) return SA_ERR_UNSUPPORTED;
   if (n < 1 || pos0 < 0 || (long long)n + pos0 > 0x7fffffffLL || !(base > 1.0) || isinf(base)) return SA_ERR_SHAPE;
   if (!(d == 64 || d == 128)) return SA_ERR_UNSUPPORTED;
   return hip_status(sa::launch_rope_table(table, n, d, base, pos0, (hipStream_t)stream));
@@ -267,6 +287,7 @@ sa_status sa_rope(const sa_desc* c, const void* Q, const void* K, const float* t
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!table || (!Q && !K) || (Q && !Q_out) || (K && !K_out)) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, Q_out, K_out}) || !aligned_to(8, {table})) return SA_ERR_UNSUPPORTED;
   if (!(interleaved == 0 || interleaved == 1) || !(inverse == 0 || inverse == 1)) return SA_ERR_SHAPE;
   const int bf16 = c->dtype == SA_BF16;
   hipError_t e = hipSuccess;
@@ -281,6 +302,7 @@ sa_status sa_permuted_copy(const sa_desc* c, const void* Q, const void* K, const
   sa_status s = validate_desc(c);
   if (s != SA_OK) return s;
   if (!Q || !K || !V || !Y) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, Y}) || !aligned_to(4, {perm})) return SA_ERR_UNSUPPORTED;
   if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
   Pass p = make_pass(c, Q, K, V, perm);
   p.Y = Y;
@@ -293,6 +315,7 @@ sa_status sa_gate_proj_fwd(const sa_desc* c, const void* Y_sa, const void* Y_swa
   if (s != SA_OK) return s;
   if (!Y_sa || !W_sa || !Y) return SA_ERR_NULL;
   if ((Y_swa == nullptr) != (W_swa == nullptr)) return SA_ERR_NULL;
+  if (!aligned_to(16, {Y_sa, Y_swa, W_sa, W_swa, Y, G_sa, G_swa})) return SA_ERR_UNSUPPORTED;
   if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
   if (((long)c->Hq * c->d) % 128 != 0) return SA_ERR_UNSUPPORTED;  // whole 128-feature tiles
   return hip_status(sa::launch_gate_proj_fwd_bf16(c->B, c->Hq, c->n, c->d, Y_sa, Y_swa, W_sa, W_swa, Y, G_sa,
@@ -310,6 +333,8 @@ sa_status sa_gate_proj_bwd(const sa_desc* c, const void* Y_sa, const void* Y_swa
   if (dual != (W_swa != nullptr) || dual != (G_swa != nullptr) || dual != (dY_swa != nullptr) ||
       dual != (dW_swa != nullptr))
     return SA_ERR_NULL;
+  if (!aligned_to(16, {Y_sa, Y_swa, W_sa, W_swa, G_sa, G_swa, dY, dY_sa, dY_swa, dW_sa, dW_swa, ws}))
+    return SA_ERR_UNSUPPORTED;
   if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
   if (((long)c->Hq * c->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
   const size_t need = sa::gate_proj_bwd_workspace_bytes(c->B, c->Hq, c->n, c->d, dual);
@@ -327,6 +352,8 @@ sa_status sa_dual_path_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (s != SA_OK) return s;
   if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
   if (!Q || !K || !V || !W_sa || !W_swa || !Y || !Y_sa || !Y_swa) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, W_sa, W_swa, Y, Y_sa, Y_swa, G_sa, G_swa}) || !aligned_to(4, {perm, LSE_sa, LSE_swa}))
+    return SA_ERR_UNSUPPORTED;
   if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
   s = sa_fwd(sa_d, Q, K, V, perm, Y_sa, LSE_sa, nullptr, 0, stream);
   if (s != SA_OK) return s;
@@ -348,6 +375,9 @@ sa_status sa_dual_path_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (!Q || !K || !V || !W_sa || !W_swa || !Y_sa || !Y_swa || !G_sa || !G_swa || !LSE_sa || !LSE_swa || !dY ||
       !dQ || !dK || !dV || !dW_sa || !dW_swa)
     return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_swa, dY, dQ, dK, dV, dW_sa, dW_swa, ws}) ||
+      !aligned_to(4, {perm, LSE_sa, LSE_swa}))
+    return SA_ERR_UNSUPPORTED;
   if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
   const DualBwdWorkspace w = dual_bwd_workspace(sa_d);
   if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
@@ -399,6 +429,9 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (s != SA_OK) return s;
   if (!same_problem(sa_d, swa_d)) return SA_ERR_SHAPE;
   if (!Q || !K || !V || !Y || !gate_sa || !gate_swa) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, Y, Y_sa, Y_swa, ws}) || !aligned_to(4, {perm, LSE_sa, LSE_swa}) ||
+      !aligned_to(gate_alignment(sa_d), {gate_sa, gate_swa}))
+    return SA_ERR_UNSUPPORTED;
   const bool bf16 = sa_d->dtype == SA_BF16;
   const size_t need = gated_fwd_workspace(sa_d);
   if (bf16 && !Y_swa && (!ws || ws_bytes < need)) return SA_ERR_WORKSPACE;
@@ -441,6 +474,9 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   }
   if (!Q || !K || !V || !Y_sa || !LSE_sa || !dY || !dQ || !dK || !dV) return SA_ERR_NULL;
   if (gated && (!gate_sa || !gate_swa || !Y_swa || !LSE_swa || !dgate_sa || !dgate_swa)) return SA_ERR_NULL;
+  if (!aligned_to(16, {Q, K, V, Y_sa, Y_swa, dY, dQ, dK, dV, ws}) || !aligned_to(4, {perm, LSE_sa, LSE_swa}) ||
+      (gated && !aligned_to(gate_alignment(sa_d), {gate_sa, gate_swa, dgate_sa, dgate_swa})))
+    return SA_ERR_UNSUPPORTED;
   const BwdWorkspace w = bwd_workspace(sa_d, gated);
   if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;

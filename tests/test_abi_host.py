@@ -148,3 +148,22 @@ def test_decode_step_arguments():
     # the workspace is sized by the capacity: it never grows when the descriptor's n shrinks
     small = sa.make_desc(2, 8, 2, 500, 128, 256)
     assert sa.sa_workspace_bytes(small, sa.SA_OP_DECODE) <= need
+
+
+def test_misaligned_pointers_are_refused_before_any_launch():
+    """Tensors are accessed 16 bytes at a time: an address off that grid is reported, not launched."""
+    d = good()
+    lib = sa.raw()
+    odd = C.c_void_p(4096 + 8)     # 8-byte aligned only
+    for kw in ("q", "k", "v", "y"):
+        assert fwd(d, **{kw: odd}) == sa.SA_ERR_UNSUPPORTED
+    # perm and LSE need their element's alignment
+    assert lib.sa_fwd(C.byref(d), FAKE, FAKE, FAKE, C.c_void_p(4098), FAKE, None, None, 0, None) == sa.SA_ERR_UNSUPPORTED
+    assert lib.sa_fwd(C.byref(d), FAKE, FAKE, FAKE, None, FAKE, C.c_void_p(4098), None, 0, None) == sa.SA_ERR_UNSUPPORTED
+    need = sa.sa_workspace_bytes(d, sa.SA_OP_DECODE)
+    assert lib.sa_decode_fwd(C.byref(d), FAKE, odd, FAKE, 10, FAKE, None, FAKE, need, None) == sa.SA_ERR_UNSUPPORTED
+    assert lib.sa_decode_fwd(C.byref(d), FAKE, FAKE, FAKE, 10, FAKE, None, odd, need, None) == sa.SA_ERR_UNSUPPORTED
+    nb = sa.sa_workspace_bytes(d, sa.SA_OP_BWD)
+    args = [FAKE] * 17
+    args[13] = odd                 # dV
+    assert lib.sa_bwd(C.byref(d), None, *args, nb, None) == sa.SA_ERR_UNSUPPORTED
