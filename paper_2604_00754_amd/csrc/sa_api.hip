@@ -18,7 +18,7 @@ bool desc_shape_ok(const sa_desc* c) {
   if (!(c->perm_B == 1 || c->perm_B == c->B)) return false;
   if (!(c->perm_H == 1 || c->perm_H == c->Hq)) return false;
   if (c->n > (1 << 30)) return false;  // slot arithmetic is done in int32 with headroom for t in (-n, 2n)
-  if ((long long)c->B * c->Hq * c->n > (1ll << 40)) return false;
+  if ((long long)c->B * c->Hq * c->n > 0x7fffffffll) return false;  // row counts are kept in 32-bit integers
   return true;
 }
 

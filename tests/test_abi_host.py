@@ -167,3 +167,12 @@ def test_misaligned_pointers_are_refused_before_any_launch():
     args = [FAKE] * 17
     args[13] = odd                 # dV
     assert lib.sa_bwd(C.byref(d), None, *args, nb, None) == sa.SA_ERR_UNSUPPORTED
+
+
+def test_row_count_must_fit_32_bits():
+    """B * Hq * n rows are counted in 32-bit integers inside the library: more is a shape error, not a launch."""
+    ok = sa.make_desc(16, 64, 8, 1 << 20, 128, 512)          # 2^30 rows
+    assert sa.sa_workspace_bytes(ok, sa.SA_OP_BWD) > 0
+    big = sa.make_desc(64, 64, 8, 1 << 20, 128, 512)         # 2^32 rows
+    assert fwd(big) == sa.SA_ERR_SHAPE
+    assert sa.sa_workspace_bytes(big, sa.SA_OP_BWD) == 0
