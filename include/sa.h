@@ -20,6 +20,8 @@
  *     Query head hq uses kv head hq / (Hq/Hkv).  Alignment is checked on the host: a tensor, weight or
  *     workspace pointer that is not 16-byte aligned, or an index / LSE / gate array not aligned to its
  *     element, gives SA_ERR_UNSUPPORTED before anything is launched.
+ *   - Size limits (SA_ERR_SHAPE beyond): n <= 2^30, B*Hq*n < 2^31 rows; the bf16 kernels additionally need one
+ *     head's rows to span less than 2 GiB (n*d*2 < 2^31, SA_ERR_UNSUPPORTED beyond).
  *   - perm: int32 [perm_B, perm_H, n]; perm[..., p] is the ORIGINAL index of the token placed at
  *     permuted slot p (the index tensor of "Q[sigma]" in Sec. 3.3; it is the inverse of the map
  *     sigma(i) = slot of token i used in Eq. 3).  perm_B in {1,B}, perm_H in {1,Hq}.  NULL means the
