@@ -99,7 +99,7 @@ sa_status sa_check_perm(const sa_desc* desc, const int32_t* perm, void* ws, size
 sa_status sa_fwd(const sa_desc* desc, const void* Q, const void* K, const void* V,
                  const int32_t* perm, void* Y, float* LSE, void* ws, size_t ws_bytes, void* stream);
 
-/* Samples the permutations of one layer on the device (Sec. 3.3 and App. A: sigma ~ Uniform(S_n),
+/* Samples the permutations of one layer on the device (Sec. 3.3 and App. B: sigma ~ Uniform(S_n),
  * drawn independently per layer, fresh at every step if the caller changes `seed`).  Writes perm
  * [perm_B, perm_H, n] in the convention of this header (perm[..., p] = original index of the token at
  * slot p).  Method: sort by random key.  Slice s = pb*perm_H + ph uses the SplitMix64 sequence
@@ -130,7 +130,7 @@ sa_status sa_permuted_copy(const sa_desc* desc, const void* Q, const void* K, co
  * Y_x[b,h,i,:] (feature (h,e) of a token lives at [b,h,i,e]).  Then
  *   g_x[t,:] = sigmoid(W_x y_x[t]),     Y[t,:] = g_sa * y_sa[t] + g_swa * y_swa[t]   (element-wise)
  * W_sa, W_swa: [dm, dm] row-major in the tensor dtype, row = output feature (the W_g of Eq. 6).
- * Y_swa = W_swa = NULL selects the single-path attention gate of App. A: Y = sigmoid(W_sa y_sa) * y_sa.
+ * Y_swa = W_swa = NULL selects the single-path attention gate of App. B: Y = sigmoid(W_sa y_sa) * y_sa.
  * G_sa, G_swa (each may be NULL): the gate values g_x, [B,Hq,n,d] in the tensor dtype, for a backward.
  * Y may not alias Y_sa or Y_swa.  bf16 with dm a multiple of 128 only (SA_ERR_UNSUPPORTED otherwise);
  * of the descriptor only B, Hq, n, d and dtype are used.  No workspace. */
@@ -150,7 +150,7 @@ sa_status sa_gate_proj_bwd(const sa_desc* desc, const void* Y_sa, const void* Y_
                            void* dY_sa, void* dY_swa, void* dW_sa, void* dW_swa,
                            void* ws, size_t ws_bytes, void* stream);
 
-/* App. A ("Attention" item; training paragraph) and Sec. 4.2: RoPE is applied to Q and K with each token's
+/* App. B ("Attention" item), App. C (training setup) and Sec. 4.2: RoPE is applied to Q and K with each token's
  * ORIGINAL position, before any shuffling; RoFormer Sec. 3.2.2 defines the rotation: pair i of the row at
  * position m turns by m * base^(-2i/d).
  * sa_rope_table fills table [n][d/2][2] (device, fp32: cos then sin of (pos0 + m) * base^(-2i/d), evaluated in

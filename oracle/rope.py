@@ -1,7 +1,7 @@
 """Oracle of rotary position embeddings on ORIGINAL token positions (test infrastructure only; numpy,
 fp64, no code shared with the HIP library).
 
-App. A (architecture, "Attention" item; training paragraph) and Sec. 4.2: RoPE (Su et al. 2023) is
+App. B (architecture, "Attention" item), App. C (training setup) and Sec. 4.2: RoPE (Su et al. 2023) is
 applied to Q and K with each token's original sequence position, before any shuffling; the
 permutation therefore never enters this operation.  RoFormer, Sec. 3.2.2: feature pair number i of a
 row at position m is rotated by the angle m * theta_i, theta_i = base^(-2 i / d), i = 0 .. d/2 - 1:

@@ -114,7 +114,7 @@ int orc_sa_bwd_dkv_rows(const orc_desc* c, const double* Q, const double* K, con
  *   g_x = sigmoid(logit_x),   Y[t,:] = g_sa * y_sa[t] + g_swa * y_swa[t]   (element-wise)
  * Y, Y_sa, Y_swa and the optional logit outputs L_sa, L_swa are [B,Hq,n,d] (feature
  * (h,e) of a token lives at [b,h,i,e]).  Y_swa = W_swa = NULL selects the
- * single-path attention gate of App. A: Y = sigmoid(W_sa y_sa) * y_sa. */
+ * single-path attention gate of App. B: Y = sigmoid(W_sa y_sa) * y_sa. */
 int orc_gate_proj_fwd(const orc_desc* c, const double* Ysa, const double* Yswa,
                       const double* Wsa, const double* Wswa, double* Y, double* Lsa, double* Lswa);
 

@@ -69,6 +69,11 @@ Pass make_pass(const sa_desc* c, const void* Q, const void* K, const void* V, co
   return p;
 }
 
+// The bf16 kernels address the rows of one head with 32-bit byte offsets.
+bool head_span_ok(const sa_desc* c) {
+  return c->dtype != SA_BF16 || (long long)c->n * c->d * 2 < (1ll << 31);
+}
+
 bool same_problem(const sa_desc* a, const sa_desc* b) {
   return a->B == b->B && a->Hq == b->Hq && a->Hkv == b->Hkv && a->n == b->n && a->d == b->d &&
          a->dtype == b->dtype && a->gate_per_dim == b->gate_per_dim && a->gate_dtype == b->gate_dtype;
@@ -124,10 +129,11 @@ DualBwdWorkspace dual_bwd_workspace(const sa_desc* c) {
   return w;
 }
 
-// The bf16 gated forward keeps the first branch's rows in fp32 until the gated sum is rounded.
+// The bf16 gated forward parks the first branch's rows (bf16, the tensor dtype) here when the caller does not
+// keep them; the second branch's epilogue reads them back for the gated sum of Eq. 5.
 size_t gated_fwd_workspace(const sa_desc* c) {
   if (c->dtype != SA_BF16) return 0;
-  return align256((size_t)c->B * c->Hq * c->n * c->d * 2);  // the first branch's rows, when the caller does not keep them
+  return align256((size_t)c->B * c->Hq * c->n * c->d * 2);
 }
 
 sa_status hip_status(hipError_t e) { return e == hipSuccess ? SA_OK : (e == hipErrorNotSupported ? SA_ERR_UNSUPPORTED : SA_ERR_HIP); }
@@ -201,6 +207,7 @@ sa_status sa_fwd(const sa_desc* c, const void* Q, const void* K, const void* V, 
   if (s != SA_OK) return s;
   if (!Q || !K || !V || !Y) return SA_ERR_NULL;
   if (!aligned_to(16, {Q, K, V, Y}) || !aligned_to(4, {perm, LSE})) return SA_ERR_UNSUPPORTED;
+  if (!head_span_ok(c)) return SA_ERR_UNSUPPORTED;
   Pass p = make_pass(c, Q, K, V, perm);
   p.Y = Y;
   p.LSE = LSE;
@@ -265,7 +272,7 @@ sa_status sa_fwd_rope(const sa_desc* c, const void* Q, const void* K, const void
   if (!aligned_to(16, {Q, K, V, Y}) || !aligned_to(4, {perm, LSE})) return SA_ERR_UNSUPPORTED;
   if (!aligned_to(8, {rope_table})) return SA_ERR_UNSUPPORTED;
   if (!(interleaved == 0 || interleaved == 1)) return SA_ERR_SHAPE;
-  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  if (c->dtype != SA_BF16 || !head_span_ok(c)) return SA_ERR_UNSUPPORTED;
   Pass p = make_pass(c, Q, K, V, perm);
   p.Y = Y;
   p.LSE = LSE;
@@ -378,7 +385,7 @@ sa_status sa_dual_path_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (!aligned_to(16, {Q, K, V, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_swa, dY, dQ, dK, dV, dW_sa, dW_swa, ws}) ||
       !aligned_to(4, {perm, LSE_sa, LSE_swa}))
     return SA_ERR_UNSUPPORTED;
-  if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0) return SA_ERR_UNSUPPORTED;
+  if (sa_d->dtype != SA_BF16 || ((long)sa_d->Hq * sa_d->d) % 128 != 0 || !head_span_ok(sa_d)) return SA_ERR_UNSUPPORTED;
   const DualBwdWorkspace w = dual_bwd_workspace(sa_d);
   if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
@@ -432,6 +439,7 @@ sa_status gated_sa_swa_fwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   if (!aligned_to(16, {Q, K, V, Y, Y_sa, Y_swa, ws}) || !aligned_to(4, {perm, LSE_sa, LSE_swa}) ||
       !aligned_to(gate_alignment(sa_d), {gate_sa, gate_swa}))
     return SA_ERR_UNSUPPORTED;
+  if (!head_span_ok(sa_d)) return SA_ERR_UNSUPPORTED;
   const bool bf16 = sa_d->dtype == SA_BF16;
   const size_t need = gated_fwd_workspace(sa_d);
   if (bf16 && !Y_swa && (!ws || ws_bytes < need)) return SA_ERR_WORKSPACE;
@@ -477,6 +485,7 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   if (!aligned_to(16, {Q, K, V, Y_sa, Y_swa, dY, dQ, dK, dV, ws}) || !aligned_to(4, {perm, LSE_sa, LSE_swa}) ||
       (gated && !aligned_to(gate_alignment(sa_d), {gate_sa, gate_swa, dgate_sa, dgate_swa})))
     return SA_ERR_UNSUPPORTED;
+  if (!head_span_ok(sa_d)) return SA_ERR_UNSUPPORTED;
   const BwdWorkspace w = bwd_workspace(sa_d, gated);
   if (!ws || ws_bytes < w.total) return SA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;

@@ -107,8 +107,8 @@ __device__ __forceinline__ void stationary_get(const bf16_t* stage, int lane, bf
 // Write a wave's transposed accumulators (lane = row c32 of the output, 4 consecutive values along
 // d per accumulator quad) as 32 bf16 rows to their original positions: src[pass] for the rows this
 // lane moves (as stationary_src gave them), orig_mine for the lane's own row c32.  `accumulate`
-// first adds what the rows already hold, in fp32, so the sum is rounded once.  The staging area is
-// private to the wave.
+// first adds what the rows already hold (the other branch's gradient, stored as bf16) in fp32 and rounds
+// the sum: two roundings in all, one per branch.  The staging area is private to the wave.
 template <class C, int D>
 __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage, bf16_t* out_head, const int* src,
                                            int orig_mine, int s0, int n, int lane, int accumulate) {
@@ -659,6 +659,7 @@ hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (p.win.circular && p.win.L + p.win.R + 1 > p.n) return hipErrorInvalidValue;
   if (!p.dO || !p.lse_in || !p.Dsum || !p.dQ || !p.dK || !p.dV) return hipErrorInvalidValue;
   if (!(p.d == 64 || p.d == 128)) return hipErrorNotSupported;
+  if ((long)p.n * p.d * 2 >= (1L << 31)) return hipErrorNotSupported;  // 32-bit row offsets inside a head
   hipError_t e = p.d == 64 ? launch_dq_t<64>(p, st) : launch_dq_t<128>(p, st);
   if (e != hipSuccess) return e;
   if (p.perm && p.perm_H != 1 && p.g > 1) {

@@ -3,7 +3,7 @@
 // One workgroup (4 wavefronts) owns 128 query rows of one (batch, KV head); a wavefront owns 32
 // consecutive PERMUTED slots of one query head.  Without grouped heads the four wavefronts take four
 // adjacent 32-slot blocks of the same query head.  When the query heads of a KV group share one
-// permutation (App. A: one permutation per layer), the wavefronts instead take the SAME slots of up
+// permutation (App. B: one permutation per layer), the wavefronts instead take the SAME slots of up
 // to four query heads of the group: all of them then need exactly the same K/V rows, so the band the
 // workgroup walks is 32 + w slots instead of 128 + w and no wavefront idles on tiles outside its own
 // band.  The workgroup walks the slots of the window band (Eq. 3) in tiles of
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   for (int kk = 0; kk < D / 16; ++kk)
     qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::QSTR + 16 * kk + 8 * g2);
   if (p.rope_table) {
-    // RoPE on the query's ORIGINAL position (App. A; Sec. 4.2), applied to the operand fragments: a lane
+    // RoPE on the query's ORIGINAL position (App. B, App. C; Sec. 4.2), applied to the operand fragments: a lane
     // holds elements 16kk + 8*g2 .. +7 of its row for every kk, so both members of a pair are its own --
     // (x[i], x[i + D/2]) sit in fragments kk and kk + D/32, (x[2i], x[2i+1]) next to each other.
     const float2* trow = reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_q * (D / 2);

@@ -44,13 +44,13 @@ __device__ __forceinline__ int swz(int row) {
 }
 
 // 16 bytes per lane from global memory (scalar base + 32-bit lane offset) straight into LDS at
-// lds_byte_addr + 16 * lane.  The address travels in M0 and must be wave-uniform.  The compiler does not
-// see this load: it is waited for with an explicit s_waitcnt vmcnt(0) before the barrier that publishes
-// the tile.
+// lds_byte_addr + 16 * lane.  The address travels in M0 and must be wave-uniform; it is handed to the
+// statement as a register operand, so the compiler knows that M0 is written here (the no-op covers the wait
+// state an LDS-DMA instruction needs after a scalar write of M0).  The compiler does not see the load
+// itself: it is waited for with an explicit s_waitcnt vmcnt before the barrier that publishes the tile.
 __device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t lane_byte_offset, uint32_t lds_byte_addr) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_byte_addr);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(m0), "v"(lane_byte_offset), "s"(base)
-               : "memory");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_byte_offset), "s"(base), "{m0}"(m0) : "memory");
 }
 __device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 

@@ -1,4 +1,4 @@
-// Rotary position embeddings on ORIGINAL token positions (App. A, "Attention" item and training
+// Rotary position embeddings on ORIGINAL token positions (App. B, "Attention" item; App. C, training
 // paragraph; Sec. 4.2): Q and K are rotated with the position each token has in the sequence before
 // any shuffling, so the permutation never enters here.  RoFormer Sec. 3.2.2: pair i of the row at
 // position m turns by m * base^(-2i/d).

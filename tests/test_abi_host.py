@@ -176,3 +176,16 @@ def test_row_count_must_fit_32_bits():
     big = sa.make_desc(64, 64, 8, 1 << 20, 128, 512)         # 2^32 rows
     assert fwd(big) == sa.SA_ERR_SHAPE
     assert sa.sa_workspace_bytes(big, sa.SA_OP_BWD) == 0
+
+
+def test_one_head_must_span_less_than_2_gib_in_bf16():
+    """The bf16 kernels form 32-bit byte offsets inside a head: n * d * 2 >= 2^31 is refused on the host, by the
+    forward and by the backward alike (the fp32 path has no such limit)."""
+    lib = sa.raw()
+    big = sa.make_desc(1, 1, 1, 1 << 23, 128, 512)           # 2^23 rows of 256 bytes = 2 GiB
+    assert fwd(big) == sa.SA_ERR_UNSUPPORTED
+    nb = sa.sa_workspace_bytes(big, sa.SA_OP_BWD)
+    assert nb > 0
+    assert lib.sa_bwd(C.byref(big), None, *([FAKE] * 17), nb, None) == sa.SA_ERR_UNSUPPORTED
+    ok = sa.make_desc(1, 1, 1, (1 << 23) - 1, 128, 512)
+    assert lib.sa_bwd(C.byref(ok), None, *([FAKE] * 17), nb - 1024, None) == sa.SA_ERR_WORKSPACE   # passes the size check

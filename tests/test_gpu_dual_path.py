@@ -69,7 +69,7 @@ def test_dual_path_layer_inference_mode():
 
 
 def test_dual_path_layer_pretraining_shape():
-    """Heads, head size and window of the pre-training setup (App. A: 16 heads of 64, w = 256), short n."""
+    """Heads, head size and window of the pre-training setup (App. B / App. C: 16 heads of 64, w = 256), short n."""
     run_layer(1, 16, 16, 1024, 64, 256, seed=4)
 
 

@@ -27,6 +27,17 @@ def pick(t, rows):
     return host64(t[ri[:, 0], ri[:, 1], ri[:, 2]])
 
 
+EDGE_SLOTS = (0, 1, 31, 32, 63, 64, 127, 128, -129, -128, -33, -32, -1)
+
+
+def edge_rows(perm_np, B, H, n, heads=None):
+    """(b, h, original index) of the tokens that sit at the first and last permuted slots and on both sides of the
+    32-, 64- and 128-slot tile edges: the rows whose bands wrap around and meet the ragged ends of the tiling."""
+    heads = range(H) if heads is None else heads
+    out = [(b, h, int(perm_np[0, 0, p % n])) for b in range(B) for h in heads for p in EDGE_SLOTS]
+    return np.array(out, np.int32)
+
+
 def fwd_fullsize(name, rows_per_head):
     from oracle import binding as orc
     from paper_2604_00754_amd import binding as sa
@@ -41,8 +52,7 @@ def fwd_fullsize(name, rows_per_head):
     Q64, K64, V64 = host64(Q), host64(K), host64(V)
     rows = synth.sample_rows(wl.B, wl.Hq, wl.n, rows_per_head, seed=11)
     # make sure the sample meets the ragged ends of the slot range (first/last tiles, wrap-around)
-    edge = np.array([(0, h, int(perm_np[0, 0, p])) for h in range(wl.Hq) for p in (0, 1, wl.n - 1)], np.int32)
-    rows = np.concatenate([rows, edge])
+    rows = np.concatenate([rows, edge_rows(perm_np, wl.B, wl.Hq, wl.n)])
     Y = torch.full_like(Q, float("nan"))
     L = torch.full((wl.B, wl.Hq, wl.n), float("nan"), device=U.DEV, dtype=torch.float32)
     for window, use_perm in ((CIRC, True), (ONE, False)):
@@ -66,7 +76,86 @@ def test_qwen3_8b_prefill_32k_sampled_rows():
 
 
 def test_qwen3_30b_prefill_128k_sampled_rows():
-    fwd_fullsize("qwen3_30b_prefill_128k", 6)
+    fwd_fullsize("qwen3_30b_prefill_128k", 64)
+
+
+def test_qwen3_8b_prefill_32k_backward_sampled_rows():
+    """sa_bwd at the headline shape (d = 128, grouped heads 4:1, n = 32768, w = 512), the call bench.py times as
+    `sa_bwd_headline_shape`: dQ on sampled query rows, dK and dV on sampled key rows of every KV head, against the
+    row-wise fp64 gradients of the oracle."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
+    print("case fullsize bwd qwen3_8b_prefill_32k", flush=True)
+    B, Hq, Hkv, n, d = wl.B, wl.Hq, wl.Hkv, wl.n, wl.d
+    Q = gpu_normal((B, Hq, n, d), 1)
+    K = gpu_normal((B, Hkv, n, d), 2)
+    V = gpu_normal((B, Hkv, n, d), 3)
+    dY = gpu_normal((B, Hq, n, d), 4)
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    desc = U.sa_desc(wl, CIRC, 1)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    dQ = torch.full_like(Q, float("nan"))
+    dK, dV = torch.full_like(K, float("nan")), torch.full_like(K, float("nan"))
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    torch.cuda.synchronize()
+    for t in (dQ, dK, dV):
+        assert torch.isfinite(t.float()).all().item()
+    Q64, K64, V64, dY64 = (host64(t) for t in (Q, K, V, dY))
+    od = U.orc_desc(wl, CIRC, 1)
+    scale = lambda r: max(1.0, float(np.abs(r).max()))
+    rows = np.concatenate([synth.sample_rows(B, Hq, n, 16, seed=21), edge_rows(perm_np, B, Hq, n)])
+    dQ_r = orc.sa_bwd_dq_rows(od, Q64, K64, V64, perm_np, dY64, rows)
+    ma, rl = U.assert_close(pick(dQ, rows), dQ_r, "bf16", "dQ rows", scale_abs=scale(dQ_r))
+    print(f"  dQ: {rows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+    krows = np.concatenate([synth.sample_rows(B, Hkv, n, 8, seed=22), edge_rows(perm_np, B, Hkv, n)])
+    dK_r, dV_r = orc.sa_bwd_dkv_rows(od, Q64, K64, V64, perm_np, dY64, krows)
+    ma, rl = U.assert_close(pick(dK, krows), dK_r, "bf16", "dK rows", scale_abs=scale(dK_r))
+    print(f"  dK: {krows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+    ma, rl = U.assert_close(pick(dV, krows), dV_r, "bf16", "dV rows", scale_abs=scale(dV_r))
+    print(f"  dV: {krows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+
+
+def test_qwen3_8b_prefill_32k_fused_query_rotation_sampled_rows():
+    """rope(K) in memory + sa_fwd_rope (Q rotated while it is staged) at the headline shape with the Qwen3 base
+    10^6, the pair of calls bench.py times as `rope_k_plus_fwd_rope`: sampled rows against rope -> attention of
+    the oracle, whose rotated rows are rounded to bf16 where both GPU paths round."""
+    from oracle import binding as orc
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
+    print("case fullsize fwd_rope qwen3_8b_prefill_32k", flush=True)
+    B, Hq, Hkv, n, d = wl.B, wl.Hq, wl.Hkv, wl.n, wl.d
+    Q = gpu_normal((B, Hq, n, d), 1)
+    K = gpu_normal((B, Hkv, n, d), 2)
+    V = gpu_normal((B, Hkv, n, d), 3)
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    desc = U.sa_desc(wl, CIRC, 1)
+    table = torch.empty((n, d // 2, 2), device=U.DEV, dtype=torch.float32)
+    sa.sa_rope_table(n, d, 1e6, 0, table)
+    Kr = torch.empty_like(K)
+    sa.sa_rope(desc, None, K, table, None, Kr)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, L)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y.float()).all().item() and torch.isfinite(L).all().item()
+    rq = synth.round_to_bf16(R.rope(host64(Q), base=1e6).astype(np.float32)).astype(np.float64)
+    rk = synth.round_to_bf16(R.rope(host64(K), base=1e6).astype(np.float32)).astype(np.float64)
+    rows = np.concatenate([synth.sample_rows(B, Hq, n, 16, seed=23), edge_rows(perm_np, B, Hq, n)])
+    Yr, Lr = orc.sa_fwd_rows(U.orc_desc(wl, CIRC, 1), rq, rk, host64(V), perm_np, rows)
+    ma, rl = U.assert_close(pick(Y, rows), Yr, "bf16", "Y rows (fused rotation)")
+    ri = torch.from_numpy(rows.astype(np.int64)).to(U.DEV)
+    la = np.abs(L[ri[:, 0], ri[:, 1], ri[:, 2]].cpu().numpy().astype(np.float64) - Lr).max()
+    assert la <= 4e-3, la
+    print(f"  {rows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e} lse {la:.1e}", flush=True)
 
 
 def test_pretrain_fwdbwd_8k_gated_sampled_rows():
@@ -99,7 +188,8 @@ def test_pretrain_fwdbwd_8k_gated_sampled_rows():
 
     Q64, K64, V64, dY64, ga64, gl64 = (host64(t) for t in (Q, K, V, dY, ga, gl))
     osa, oswa = U.orc_desc(wl, CIRC, 1), U.orc_desc(wl, ONE, 1)
-    rows = synth.sample_rows(B, H, n, 6, seed=12)
+    rows = np.concatenate([synth.sample_rows(B, H, n, 6, seed=12), edge_rows(perm_np, B, H, n, heads=(0, 5, H - 1)),
+                           np.array([(b, h, i) for b in (0, B - 1) for h in (0, H - 1) for i in (0, 1, 255, 256, n - 1)], np.int32)])
     m = rows.shape[0]
     rdesc = orc.desc(1, 1, 1, m, d, 1)                      # the sampled rows seen as one small tensor
     Ysa_r, _ = orc.sa_fwd_rows(osa, Q64, K64, V64, perm_np, rows)
@@ -118,7 +208,8 @@ def test_pretrain_fwdbwd_8k_gated_sampled_rows():
         orc.sa_bwd_dq_rows(oswa, Q64, K64, V64, None, dYswa, rows)
     scale = lambda r: max(1.0, float(np.abs(r).max()))
     U.assert_close(pick(dQ, rows), dQ_r, "bf16", "dQ rows", scale_abs=scale(dQ_r))
-    krows = synth.sample_rows(B, H, n, 2, seed=13)
+    krows = np.concatenate([synth.sample_rows(B, H, n, 2, seed=13), edge_rows(perm_np, B, H, n, heads=(0, H - 1)),
+                            np.array([(0, 3, i) for i in (0, 127, 128, n - 256, n - 1)], np.int32)])
     dKa, dVa = orc.sa_bwd_dkv_rows(osa, Q64, K64, V64, perm_np, dYsa, krows)
     dKl, dVl = orc.sa_bwd_dkv_rows(oswa, Q64, K64, V64, None, dYswa, krows)
     U.assert_close(pick(dK, krows), dKa + dKl, "bf16", "dK rows", scale_abs=scale(dKa + dKl))

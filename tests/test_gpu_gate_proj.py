@@ -59,7 +59,7 @@ def test_gate_proj_saturating_and_zero_weights():
 
 
 def test_gate_proj_pretraining_width():
-    """d_model = 1024 (16 heads of 64) as in the paper's pre-training setup (App. A), a few token tiles."""
+    """d_model = 1024 (16 heads of 64) as in the paper's pre-training setup (App. B, App. C), a few token tiles."""
     run_case(1, 16, 1000, 64, seed=11)
 
 

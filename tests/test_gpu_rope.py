@@ -1,4 +1,4 @@
-"""GPU parity of sa_rope_table / sa_rope (RoPE on original positions, App. A / Sec. 4.2; RoFormer Sec. 3.2.2)
+"""GPU parity of sa_rope_table / sa_rope (RoPE on original positions, App. B, App. C / Sec. 4.2; RoFormer Sec. 3.2.2)
 against the fp64 numpy oracle, through the C ABI."""
 import numpy as np
 import pytest

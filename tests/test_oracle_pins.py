@@ -525,7 +525,7 @@ def test_gate_projection_against_matmul_and_closed_forms():
     E = np.zeros((dm, dm)); E[:, 5] = 1.0        # every output feature reads input feature 5 = (head 1, e 1)
     g = sig(Ysa[:, 1, :, 1])[:, None, :, None]   # one gate value per token, broadcast over heads and e
     np.testing.assert_allclose(orc.gate_proj_fwd(c, Ysa, Yswa, E, Z), g * Ysa + 0.5 * Yswa, atol=1e-14)
-    # single path (App. A attention gate) = dual path with a vanishing second branch
+    # single path (App. B attention gate) = dual path with a vanishing second branch
     single = orc.gate_proj_fwd(c, Ysa, None, Wsa, None)
     np.testing.assert_allclose(single, orc.gate_proj_fwd(c, Ysa, np.zeros_like(Ysa), Wsa, Wswa), atol=1e-15)
 
