@@ -50,7 +50,9 @@ typedef enum {
   SA_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for       */
   SA_ERR_WORKSPACE = 4,   /* workspace missing or smaller than required       */
   SA_ERR_BAD_PERM = 5,    /* sa_check_perm found a slice that is no bijection */
-  SA_ERR_HIP = 6          /* a HIP call or launch failed                      */
+  SA_ERR_HIP = 6,         /* a HIP call or launch failed                      */
+  SA_ERR_STATIC_LIMIT = 7 /* sa_decode_fwd_static: the request needs more scratch memory than
+                             SA_STATIC_SCRATCH_BYTES                          */
 } sa_status;
 
 typedef enum { SA_BF16 = 0, SA_F32 = 1 } sa_dtype;
@@ -202,6 +204,20 @@ sa_status sa_dual_path_bwd(const sa_desc* sa, const sa_desc* swa, const void* Q,
  * size depends on the capacity, not on len). */
 sa_status sa_decode_fwd(const sa_desc* desc, const void* q, const void* K, const void* V, int32_t len, void* Y,
                         float* LSE, void* ws, size_t ws_bytes, void* stream);
+
+/* sa_decode_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as sa_decode_fwd, but the partial results of the chunks live in a buffer of
+ * SA_STATIC_SCRATCH_BYTES that is part of the library image (one copy per GPU the library runs on, held
+ * until the process ends).  The call allocates and frees nothing.
+ * A descriptor whose sa_workspace_bytes(desc, SA_OP_DECODE) exceeds SA_STATIC_SCRATCH_BYTES is refused with
+ * SA_ERR_STATIC_LIMIT before anything is launched (8 MiB covers, e.g., B = 1 with 32 heads of 128 over a
+ * cache of 131072 rows: 4.3 MB).  The first call on a device looks the buffer's address up (no allocation;
+ * make that call outside a graph capture).  All calls on one GPU share the one buffer: calls that overlap
+ * on the same GPU (different streams or threads) race; calls on one stream are ordered and safe. */
+#define SA_STATIC_SCRATCH_BYTES (8u << 20)
+sa_status sa_decode_fwd_static(const sa_desc* desc, const void* q, const void* K, const void* V, int32_t len,
+                               void* Y, float* LSE, void* stream);
 
 /* sa_decode_fwd for a batch whose sequences have different numbers of cached rows: lens [B] (int32, device
  * memory) gives the rows of each sequence, max_len (host, 1 <= max_len <= n) an upper bound of them that sizes the

@@ -12,6 +12,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsa.so")
 
 SA_OK, SA_ERR_NULL, SA_ERR_SHAPE, SA_ERR_UNSUPPORTED, SA_ERR_WORKSPACE, SA_ERR_BAD_PERM, SA_ERR_HIP = range(7)
+SA_ERR_STATIC_LIMIT = 7
+SA_STATIC_SCRATCH_BYTES = 8 << 20
 SA_BF16, SA_F32 = 0, 1
 SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
@@ -21,7 +23,8 @@ SA_OP_DECODE = 9
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
            "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
-           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd", "sa_decode_fwd_varlen")
+           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd", "sa_decode_fwd_varlen",
+           "sa_decode_fwd_static")
 
 
 class sa_desc(C.Structure):
@@ -73,6 +76,8 @@ def _load():
     lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.sa_decode_fwd.restype = C.c_int
     lib.sa_decode_fwd.argtypes = [dp, vp, vp, vp, C.c_int32, vp, vp, vp, sz, vp]
+    lib.sa_decode_fwd_static.restype = C.c_int
+    lib.sa_decode_fwd_static.argtypes = [dp, vp, vp, vp, C.c_int32, vp, vp, vp]
     lib.sa_decode_fwd_varlen.restype = C.c_int
     lib.sa_decode_fwd_varlen.argtypes = [dp, vp, vp, vp, ip, C.c_int32, vp, vp, vp, sz, vp]
     lib.swa_fwd.restype = C.c_int
@@ -184,6 +189,11 @@ def sa_decode_fwd(desc, q, K, V, length, Y, LSE, ws):
     _check(_lib.sa_decode_fwd(C.byref(desc), _ptr(q), _ptr(K), _ptr(V), int(length), _ptr(Y), _ptr(LSE), _ptr(ws),
                               (ws.numel() * ws.element_size()) if ws is not None else 0, _stream()),
            "sa_decode_fwd")
+
+
+def sa_decode_fwd_static(desc, q, K, V, length, Y, LSE):
+    _check(_lib.sa_decode_fwd_static(C.byref(desc), _ptr(q), _ptr(K), _ptr(V), int(length), _ptr(Y), _ptr(LSE),
+                                     _stream()), "sa_decode_fwd_static")
 
 
 def sa_decode_fwd_varlen(desc, q, K, V, lens, max_len, Y, LSE, ws):

@@ -2,7 +2,9 @@
 // Validation happens here, before any launch; kernels live in the other files of this directory.
 #include <math.h>
 
+#include <atomic>
 #include <initializer_list>
+#include <mutex>
 
 #include "sa_common.h"
 
@@ -136,6 +138,33 @@ size_t gated_fwd_workspace(const sa_desc* c) {
   return align256((size_t)c->B * c->Hq * c->n * c->d * 2);
 }
 
+// Scratch memory of sa_decode_fwd_static: one copy per GPU the library runs on, held until the process ends.
+// In host code the array's name is only a stand-in for the device symbol; the address a kernel may use is
+// looked up once per device (static_scratch_ptr) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)SA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, or nullptr (with *err set) if it cannot be had.
+void* static_scratch_ptr(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (*err != hipSuccess || !ptr) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  return ptr;
+}
+
 sa_status hip_status(hipError_t e) { return e == hipSuccess ? SA_OK : (e == hipErrorNotSupported ? SA_ERR_UNSUPPORTED : SA_ERR_HIP); }
 
 hipError_t run_fwd(const sa_desc* c, const Pass& p, hipStream_t st) {
@@ -159,6 +188,7 @@ const char* sa_status_string(sa_status s) {
     case SA_ERR_WORKSPACE: return "workspace missing or too small";
     case SA_ERR_BAD_PERM: return "perm is not a bijection of 0..n-1";
     case SA_ERR_HIP: return "HIP call failed";
+    case SA_ERR_STATIC_LIMIT: return "request needs more scratch memory than the static buffer holds";
   }
   return "unknown status";
 }
@@ -222,6 +252,23 @@ sa_status decode_common(const sa_desc* c, const void* q, const void* K, const vo
 sa_status sa_decode_fwd(const sa_desc* c, const void* q, const void* K, const void* V, int32_t len, void* Y,
                         float* LSE, void* ws, size_t ws_bytes, void* stream) {
   return decode_common(c, q, K, V, nullptr, len, Y, LSE, ws, ws_bytes, stream);
+}
+
+sa_status sa_decode_fwd_static(const sa_desc* c, const void* q, const void* K, const void* V, int32_t len, void* Y,
+                               float* LSE, void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  // the size is judged before the device is touched: a request that cannot fit never reaches the GPU
+  const size_t need = sa_workspace_bytes(c, SA_OP_DECODE);
+  if (need > kStaticScratchBytes) return SA_ERR_STATIC_LIMIT;
+  if (!q || !K || !V || !Y) return SA_ERR_NULL;
+  if (len < 1 || len > c->n) return SA_ERR_SHAPE;
+  hipError_t e = hipSuccess;
+  void* ptr = static_scratch_ptr(&e);
+  if (!ptr) return SA_ERR_HIP;
+  // every partial result the merge kernel reads is written by the partial kernel of the same call, so nothing
+  // in the buffer has to start at zero
+  return decode_common(c, q, K, V, nullptr, len, Y, LSE, ptr, kStaticScratchBytes, stream);
 }
 
 sa_status sa_decode_fwd_varlen(const sa_desc* c, const void* q, const void* K, const void* V, const int32_t* lens,

@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_status_strings():
-    for code in range(7):
+    for code in range(8):
         assert sa.status_string(code) and sa.status_string(code) != "unknown status"
     assert sa.status_string(99) == "unknown status"
 
@@ -189,3 +189,17 @@ def test_one_head_must_span_less_than_2_gib_in_bf16():
     assert lib.sa_bwd(C.byref(big), None, *([FAKE] * 17), nb, None) == sa.SA_ERR_UNSUPPORTED
     ok = sa.make_desc(1, 1, 1, (1 << 23) - 1, 128, 512)
     assert lib.sa_bwd(C.byref(ok), None, *([FAKE] * 17), nb - 1024, None) == sa.SA_ERR_WORKSPACE   # passes the size check
+
+
+def test_static_decode_refuses_what_its_buffer_cannot_hold():
+    """sa_decode_fwd_static judges the size on the host, before it touches the device."""
+    lib = sa.raw()
+    fits = sa.make_desc(1, 32, 4, 131072, 128, 1024)
+    assert 0 < sa.sa_workspace_bytes(fits, sa.SA_OP_DECODE) <= sa.SA_STATIC_SCRATCH_BYTES
+    big = sa.make_desc(16, 32, 8, 131072, 128, 1024)
+    assert sa.sa_workspace_bytes(big, sa.SA_OP_DECODE) > sa.SA_STATIC_SCRATCH_BYTES
+    assert lib.sa_decode_fwd_static(C.byref(big), FAKE, FAKE, FAKE, 16, FAKE, None, None) == sa.SA_ERR_STATIC_LIMIT
+    assert sa.status_string(sa.SA_ERR_STATIC_LIMIT).startswith("request needs more scratch")
+    assert lib.sa_decode_fwd_static(C.byref(fits), None, FAKE, FAKE, 16, FAKE, None, None) == sa.SA_ERR_NULL
+    assert lib.sa_decode_fwd_static(C.byref(fits), FAKE, FAKE, FAKE, 0, FAKE, None, None) == sa.SA_ERR_SHAPE
+    assert lib.sa_decode_fwd_static(None, FAKE, FAKE, FAKE, 1, FAKE, None, None) == sa.SA_ERR_NULL
