@@ -18,18 +18,11 @@
 namespace sa {
 namespace {
 
-#ifndef DKV_WAVES
-#define DKV_WAVES 2
-#endif
-#ifndef DQ128_WAVES
-#define DQ128_WAVES 2
-#endif
-#ifndef DKV128_WAVES
-#define DKV128_WAVES 1
-#endif
-#ifndef DKV_BN
-#define DKV_BN 128
-#endif
+// Waves per SIMD the kernels are compiled for (register budget 512 / waves per lane), and the streamed slots per
+// tile of the dK/dV kernel.  At d = 128 the dK/dV kernel holds 128 accumulators and 64 stationary operand
+// registers per lane: one wave per SIMD.
+constexpr int DQ64_WAVES = 3, DQ128_WAVES = 2, DKV64_WAVES = 2, DKV128_WAVES = 1;
+constexpr int DKV64_BN = 128, DKV128_BN = 64;
 constexpr int BM = 128;  // stationary slots per workgroup
 constexpr int NT = 256;
 
@@ -146,7 +139,7 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
 
 // ------------------------------------------------------------------------------------------ dQ
 template <int D, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
+__global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_dq_mfma_bf16_kernel(const Pass p, const int num_qt, const long total_work,
                                                                                             const int hshift) {
   using C = Cfg<D, 64>;
   constexpr int BN = C::BN;
@@ -289,12 +282,24 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
       f32x16 sacc, dpacc;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+      {
+        // the operand reads of step kk + 1 are under way while the matrix instructions of step kk issue (left
+        // to itself the compiler reads every step into the same registers, one LDS latency per step)
+        bf16x8 ka[2], va[2];
+        ka[0] = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[0]);
+        va[0] = *reinterpret_cast<const bf16x8*>(Vs + 32 * kb * D + koff[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[kk]);
-        sacc = mfma_bf16(ka, qf[kk], sacc);    // S^T = K Q^T
-        const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vs + 32 * kb * D + koff[kk]);
-        dpacc = mfma_bf16(va, gf[kk], dpacc);  // dP^T = V dO^T
+        for (int kk = 0; kk < D / 16; ++kk) {
+          if (kk + 1 < D / 16) {
+            ka[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(Ks + 32 * kb * D + koff[kk + 1]);
+            va[(kk + 1) & 1] = *reinterpret_cast<const bf16x8*>(Vs + 32 * kb * D + koff[kk + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          sacc = mfma_bf16(ka[kk & 1], qf[kk], sacc);    // S^T = K Q^T
+          dpacc = mfma_bf16(va[kk & 1], gf[kk], dpacc);  // dP^T = V dO^T
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       if (CAUSAL == CAUSAL_I32) {
 #pragma unroll
@@ -341,10 +346,20 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
         dsf0 = pack_b_operand(ds);
         dsf1 = pack_b_operand(ds + 8);
       }
+      {  // dQ^T += K^T dS^T: the half of the block's key rows outermost, so that two products on the same
+         // accumulator are D / 32 instructions apart; the operand of product m + 1 is read before product m issues
+        constexpr int NPQ = 2 * (D / 32);
+        bf16x8 ka[2];
+        ka[0] = lds_read_transposed_swz(Ks + (32 * kb) * D, troff[0]);
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db) {  // dQ^T += K^T dS^T
-        dqacc[db] = mfma_bf16(lds_read_transposed_swz(Ks + (32 * kb) * D, troff[db]), dsf0, dqacc[db]);
-        dqacc[db] = mfma_bf16(lds_read_transposed_swz(Ks + (32 * kb + 16) * D, troff[db]), dsf1, dqacc[db]);
+        for (int m = 0; m < NPQ; ++m) {
+          if (m + 1 < NPQ) {
+            ka[(m + 1) & 1] = lds_read_transposed_swz(Ks + (32 * kb + 16 * ((m + 1) / (D / 32))) * D, troff[(m + 1) % (D / 32)]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          dqacc[m % (D / 32)] = mfma_bf16(ka[m & 1], m < D / 32 ? dsf0 : dsf1, dqacc[m % (D / 32)]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   }
@@ -356,8 +371,8 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : 3) void bwd_dq_mfma_bf
 
 // --------------------------------------------------------------------------------------- dK, dV
 template <int D, int CAUSAL>
-__global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_dkv_mfma_bf16_kernel(const Pass p, const int num_kt, const long total_work) {
-  using C = Cfg<D, D == 64 ? DKV_BN : 64>;
+__global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV64_WAVES) void bwd_dkv_mfma_bf16_kernel(const Pass p, const int num_kt, const long total_work) {
+  using C = Cfg<D, D == 64 ? DKV64_BN : DKV128_BN>;
   constexpr int BN = C::BN;
   __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
 
@@ -398,7 +413,10 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { dkacc[db][i] = 0.f; dvacc[db][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) {
+      dkacc[db][i] = 0.f;
+      dvacc[db][i] = 0.f;
+    }
 
   const int32_t* perm = nullptr;
   const int hg_begin = p.hq_only >= 0 ? p.hq_only : 0;
@@ -410,6 +428,32 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
   int koff[D / 16], troff[D / 32][2];
   swizzled_row_offsets<D>(lane, koff);
   swizzled_tr_offsets<D>(lane, troff);
+  // The products of one block on the output accumulators, as a list: m = half * NP/2 + r, where half selects
+  // the block's query rows 0-15 / 16-31 (operand halves 0 / 1 of P and dS) and r runs over the 32-column
+  // blocks of the outputs (dV and dK alternate when both are formed), so that two products on the same
+  // accumulator are NP/2 instructions apart.
+  constexpr int NP = 4 * (D / 32);
+  constexpr int PPS = NP / 8;  // products per slot
+  constexpr int PF = 1;  // how many steps ahead the operands of S and dP are read (deeper: no gain)
+  // One wave per SIMD has nobody to hide its latencies behind: there the products of a block on the outputs
+  // wait for the vector work of the next block (16 more registers; at two waves per SIMD they would spill),
+  // and S and dP are pinned to the vector half of the register file.
+  constexpr bool DEFER = D == 128 && DKV128_WAVES == 1;
+  constexpr bool S_IN_VEC = DEFER;
+  static_assert(NP % 8 == 0, "a whole number of products per slot");
+  auto product_operand = [&](const int m, const bf16_t* Qb, const bf16_t* Gb) -> bf16x8 {
+    const int half = m / (NP / 2), r = m % (NP / 2);
+    const int db = r / 2;
+    const bool is_dv = (r % 2) == 0;
+    return lds_read_transposed_swz((is_dv ? Gb : Qb) + 16 * half * D, troff[db]);
+  };
+  auto product = [&](const int m, const bf16x8 a, const bf16x8* pf, const bf16x8* dsf) {
+    const int half = m / (NP / 2), r = m % (NP / 2);
+    const int db = r / 2;
+    const bool is_dv = (r % 2) == 0;
+    if (is_dv) dvacc[db] = mfma_bf16(a, pf[half], dvacc[db]);
+    else dkacc[db] = mfma_bf16(a, dsf[half], dkacc[db]);
+  };
   for (int hg = hg_begin; hg < hg_end; ++hg) {
     const int hq = hk * p.g + hg;
     const int32_t* __restrict__ perm_h =
@@ -440,26 +484,32 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
     int idx[C::NV];
     int pq_w = 0, pq_n = 0;
     float lse_w = 0.f, dd_w = 0.f;
-    // requests the tile whose row indices are in idx and publishes the per-slot values held in *_w
-    auto request_tile = [&](const int buf) {
-#pragma unroll
-      for (int v = 0; v < C::NV; ++v) {
-        const uint32_t goff = (uint32_t)idx[v] * (uint32_t)(D * 2) + ld_chunk_off;
-        const uint32_t dst = lds0 + buf * C::BUF_BYTES + (v * C::RPP + wave * C::WRPP) * (D * 2);
-        load_to_lds_16(Qh, goff, dst);
-        load_to_lds_16(dOh, goff, dst + C::TILE_BYTES);
-      }
+    // instruction j of the request for a tile: j < NV the Q rows whose indices are in idx[j], j >= NV the dO
+    // rows of idx[j - NV]
+    auto request_instr = [&](const int j, const int buf) {
+      const int v = j % C::NV;
+      const uint32_t goff = (uint32_t)idx[v] * (uint32_t)(D * 2) + ld_chunk_off;
+      const uint32_t at = buf * C::BUF_BYTES + (v * C::RPP + wave * C::WRPP) * (D * 2) + (j < C::NV ? 0 : C::TILE_BYTES);
+      load_to_lds_16(j < C::NV ? Qh : dOh, goff, lds0 + at);
+    };
+    // publishes the per-slot values held in *_w beside the tile that is being requested
+    auto publish_slots = [&](const int buf) {
       if (tid < BN) {
         char* slot = smem + C::AREA_BYTES + buf * C::SLOT_BYTES;
         if (CAUSAL == CAUSAL_I32) reinterpret_cast<int*>(slot)[tid] = pq_w;
         if (CAUSAL == CAUSAL_I16) reinterpret_cast<short*>(slot)[pq_pos] = (short)(pq_w - 32767);
-        reinterpret_cast<float*>(slot + BN * 4)[tid] = lse_w;
+        reinterpret_cast<float*>(slot + BN * 4)[tid] = lse_w * kLog2e;
         reinterpret_cast<float*>(slot + 2 * BN * 4)[tid] = -dd_w;  // dP starts from -D, so that the product leaves dP - D
       }
     };
+    auto request_tile = [&](const int buf) {
+#pragma unroll
+      for (int j = 0; j < 2 * C::NV; ++j) request_instr(j, buf);
+      publish_slots(buf);
+    };
     auto load_slot_values = [&]() {  // LSE and D of the slot whose position is in pq_w
       if (tid < BN) {
-        lse_w = lse_h[pq_w] * kLog2e;
+        lse_w = lse_h[pq_w];  // used (scaled) when the tile is published: no wait for it among the requests
         dd_w = dd_h[pq_w];
       }
     };
@@ -507,8 +557,13 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
       // everyone is done with the other buffer (the tile before, the staging of the prologue)
       wait_all_loads();
       __syncthreads();
-      if (tile + 1 < ntiles) {
-        request_tile(buf ^ 1);
+      // the next tile (a direct-to-LDS load holds the wave's issue port for about 100 cycles here, wherever in
+      // the tile it is placed and also when the rows travel through registers instead)
+      const bool more = tile + 1 < ntiles;
+      if (more) {
+#pragma unroll
+        for (int j = 0; j < 2 * C::NV; ++j) request_instr(j, buf ^ 1);
+        publish_slots(buf ^ 1);
         pq_w = pq_n;
         load_slot_values();
 #pragma unroll
@@ -523,6 +578,9 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
       const float* lse_lds = reinterpret_cast<const float*>(slot + BN * 4);
       const float* dd_lds = reinterpret_cast<const float*>(slot + 2 * BN * 4);
       const int s0 = s_lo + tile * BN;
+      bool pend = false;
+      bf16x8 pfP[2], dsfP[2];
+      const bf16_t *QsP = Qs, *GsP = Gs;
 #pragma unroll
       for (int qb = 0; qb < BN / 32; ++qb) {
         const int sb0 = s0 + 32 * qb;
@@ -537,12 +595,35 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
 #pragma unroll
           for (int x = 0; x < 4; ++x) { sacc[4 * mq + x] = 0.f; dpacc[4 * mq + x] = d4[x]; }
         }
+        {
+          // the operand reads of steps kk + 1 .. kk + PF are under way while the matrix instructions of step kk issue
+          // (left to itself the compiler reads every step into the same registers, one LDS latency per step)
+          constexpr int NB = PF + 1;
+          bf16x8 qa[NB], ga[NB];
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) {
-          const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qs + 32 * qb * D + koff[kk]);
-          sacc = mfma_bf16(qa, kf[kk], sacc);    // S = Q K^T
-          const bf16x8 ga = *reinterpret_cast<const bf16x8*>(Gs + 32 * qb * D + koff[kk]);
-          dpacc = mfma_bf16(ga, vf[kk], dpacc);  // dP = dO V^T
+          for (int j = 0; j < PF; ++j) {
+            qa[j] = *reinterpret_cast<const bf16x8*>(Qs + 32 * qb * D + koff[j]);
+            ga[j] = *reinterpret_cast<const bf16x8*>(Gs + 32 * qb * D + koff[j]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int kk = 0; kk < D / 16; ++kk) {
+            if (kk + PF < D / 16) {
+              qa[(kk + PF) % NB] = *reinterpret_cast<const bf16x8*>(Qs + 32 * qb * D + koff[kk + PF]);
+              ga[(kk + PF) % NB] = *reinterpret_cast<const bf16x8*>(Gs + 32 * qb * D + koff[kk + PF]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (S_IN_VEC) {
+              if (kk == 0) mfma_bf16_v_first(qa[0], kf[0], sacc);
+              else mfma_bf16_v(qa[kk % NB], kf[kk], sacc);
+              mfma_bf16_v(ga[kk % NB], vf[kk], dpacc);
+            } else {
+              sacc = mfma_bf16(qa[kk % NB], kf[kk], sacc);    // S = Q K^T
+              dpacc = mfma_bf16(ga[kk % NB], vf[kk], dpacc);  // dP = dO V^T
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (S_IN_VEC) matrix_results_to_vector(sacc, dpacc);
         }
         // accumulator i is query row 32*qb + 8*(i/4) + 4*g2 + i%4 of the tile, key column = lane
         if (CAUSAL == CAUSAL_I32) {
@@ -563,43 +644,65 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV_WAVES) void bwd_d
             if (u > srange || smax < smin) sacc[i] = -INFINITY;
           }
         }
-        float pe[16], ds[16];
+        // P and dS of this block, pair by pair (accumulators 2e, 2e+1), while the matrix pipe works off the
+        // products of the block before it (dV^T += dO^T P, dK^T += Q^T dS: contraction over its 32 query rows),
+        // whose operands wait in pfP / dsfP: one slot per pair = its share of the matrix instructions, the
+        // operand reads of the next slot, the pair's vector work; nothing moves across a slot boundary.
+        f32x4 l4[4];
 #pragma unroll
-        for (int mq = 0; mq < 4; ++mq) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_lds + 32 * qb + 8 * mq + 4 * g2);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) {
-            const int i = 4 * mq + x;
-            pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[i], cs, -l4[x]));
-            ds[i] = pe[i] * dpacc[i];  // dpacc = dP - D
-          }
-        }
-        bf16x8 pf0, pf1, dsf0, dsf1;
+        for (int mq = 0; mq < 4; ++mq) l4[mq] = *reinterpret_cast<const f32x4*>(lse_lds + 32 * qb + 8 * mq + 4 * g2);
+        u32x4 ia = {0, 0, 0, 0}, ib = {0, 0, 0, 0};
         if (CAUSAL == CAUSAL_I16) {
           const uint32_t* pq16 = reinterpret_cast<const uint32_t*>(pq16_lds) + 16 * qb + 8 * g2;
-          const u32x4 ia = *reinterpret_cast<const u32x4*>(pq16), ib = *reinterpret_cast<const u32x4*>(pq16 + 4);
-          u32x4 wp[2], wd[2];
+          ia = *reinterpret_cast<const u32x4*>(pq16);
+          ib = *reinterpret_cast<const u32x4*>(pq16 + 4);
+        }
+        u32x4 wp[2], wd[2];
+        auto pair = [&](const int e) {
+          const int i0 = 2 * e, i1 = 2 * e + 1;
+          const float pe0 = __builtin_amdgcn_exp2f(fmaf(sacc[i0], cs, -l4[i0 >> 2][i0 & 3]));
+          const float pe1 = __builtin_amdgcn_exp2f(fmaf(sacc[i1], cs, -l4[i1 >> 2][i1 & 3]));
+          uint32_t vis = 0xffffffffu;
+          if (CAUSAL == CAUSAL_I16) {
+            const s16x2 pq2 = __builtin_bit_cast(s16x2, e < 4 ? ia[e & 3] : ib[e & 3]);
+            vis = __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(okm1, pq2) >> (short)15);
+          }
+          wp[e >> 2][e & 3] = pack_bf16(pe0, pe1) & vis;
+          wd[e >> 2][e & 3] = pack_bf16(pe0 * dpacc[i0], pe1 * dpacc[i1]) & vis;  // dpacc = dP - D
+        };
+        if (pend) {
+          bf16x8 aop[2][PPS];
+#pragma unroll
+          for (int j = 0; j < PPS; ++j) aop[0][j] = product_operand(j, QsP, GsP);
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            const s16x2 pq2 = __builtin_bit_cast(s16x2, e < 4 ? ia[e & 3] : ib[e & 3]);
-            const uint32_t vis = __builtin_bit_cast(uint32_t, __builtin_elementwise_sub_sat(okm1, pq2) >> (short)15);
-            wp[e >> 2][e & 3] = pack_bf16(pe[2 * e], pe[2 * e + 1]) & vis;
-            wd[e >> 2][e & 3] = pack_bf16(ds[2 * e], ds[2 * e + 1]) & vis;
-          }
-          pf0 = __builtin_bit_cast(bf16x8, wp[0]); pf1 = __builtin_bit_cast(bf16x8, wp[1]);
-          dsf0 = __builtin_bit_cast(bf16x8, wd[0]); dsf1 = __builtin_bit_cast(bf16x8, wd[1]);
-        } else {
-          pf0 = pack_b_operand(pe); pf1 = pack_b_operand(pe + 8);
-          dsf0 = pack_b_operand(ds); dsf1 = pack_b_operand(ds + 8);
-        }
+            if (e + 1 < 8) {
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-          // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over the 32 query rows of the block)
-          dvacc[db] = mfma_bf16(lds_read_transposed_swz(Gs + (32 * qb) * D, troff[db]), pf0, dvacc[db]);
-          dvacc[db] = mfma_bf16(lds_read_transposed_swz(Gs + (32 * qb + 16) * D, troff[db]), pf1, dvacc[db]);
-          dkacc[db] = mfma_bf16(lds_read_transposed_swz(Qs + (32 * qb) * D, troff[db]), dsf0, dkacc[db]);
-          dkacc[db] = mfma_bf16(lds_read_transposed_swz(Qs + (32 * qb + 16) * D, troff[db]), dsf1, dkacc[db]);
+              for (int j = 0; j < PPS; ++j) aop[(e + 1) & 1][j] = product_operand((e + 1) * PPS + j, QsP, GsP);
+            }
+#pragma unroll
+            for (int j = 0; j < PPS; ++j) product(e * PPS + j, aop[e & 1][j], pfP, dsfP);
+            pair(e);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pair(e);
         }
+        pfP[0] = __builtin_bit_cast(bf16x8, wp[0]); pfP[1] = __builtin_bit_cast(bf16x8, wp[1]);
+        dsfP[0] = __builtin_bit_cast(bf16x8, wd[0]); dsfP[1] = __builtin_bit_cast(bf16x8, wd[1]);
+        QsP = Qs + 32 * qb * D;
+        GsP = Gs + 32 * qb * D;
+        if (DEFER) {
+          pend = true;
+        } else {
+#pragma unroll
+          for (int m = 0; m < NP; ++m) product(m, product_operand(m, QsP, GsP), pfP, dsfP);
+        }
+      }
+      if (pend) {  // the last block of the tile: its rows are overwritten after the next barrier
+#pragma unroll
+        for (int m = 0; m < NP; ++m) product(m, product_operand(m, QsP, GsP), pfP, dsfP);
       }
     }
   }

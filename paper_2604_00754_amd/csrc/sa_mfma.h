@@ -15,6 +15,21 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// The same product written as an instruction, with the accumulator pinned to the vector half of the register
+// file.  A kernel that is allowed more than 256 registers per lane gets matrix results in the accumulator half
+// by default, and every vector instruction that uses them (scores, probabilities) then needs a copy first.
+// The compiler does not know what the statement is: the wait states between the last product of a chain and the
+// first vector instruction that reads its result are supplied by matrix_results_to_vector().
+__device__ __forceinline__ void mfma_bf16_v_first(const bf16x8 a, const bf16x8 b, f32x16& acc) {  // acc = A B
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_bf16_v(const bf16x8 a, const bf16x8 b, f32x16& acc) {  // acc += A B
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void matrix_results_to_vector(f32x16& x, f32x16& y) {
+  asm volatile("s_nop 11" : "+v"(x), "+v"(y));
+}
+
 // Transposing LDS read (ds_read_b64_tr_b16): within a group of 16 lanes, lane i receives element
 // (i % 4) of the 8-byte words addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group.
 __device__ __forceinline__ s16x4 lds_read_tr16(const bf16_t* p) {
