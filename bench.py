@@ -387,7 +387,6 @@ def main():
             sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, LSE)
         _, rf_ms = time_side(rope_then_attention, max(10, args.steps // 4), 5)
         other.update({"rope_k_plus_fwd_rope_ms": rf_ms, "rope_qk_plus_fwd_ms": rp_ms + ms_per_step})
-        del Y2, Kr, table
         # backward of the headline shape (not a workload of the paper, which trains at d = 64): dQ, dK, dV from dY
         dYh = torch.randn(Q.shape, device=dev, dtype=torch.float32).to(torch.bfloat16)
         dQh, dKh, dVh = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
@@ -397,7 +396,19 @@ def main():
                                              dQh, dKh, dVh, None, None, wsh), max(5, args.steps // 20), 2)
         other.update({"sa_bwd_headline_shape_ms": bw_ms,
                       "sa_fwdbwd_headline_shape_band_tflops": 3.5 * band_flop / ((ms_per_step + bw_ms) * 1e-3) / 1e12})
-        del dYh, dQh, dKh, dVh, wsh
+        # the training sequence with RoPE on original positions: sa_bwd on rotated Q, K followed by the inverse
+        # rotation of dQ and dK in memory, against sa_bwd_rope (Q rotated while staged, dQ and dK turned back in
+        # the epilogues of the two kernels)
+        sa.sa_rope(desc, Q, K, table, Y2, Kr)
+        def bwd_then_inverse_rope():
+            sa.sa_bwd(desc, None, Y2, Kr, V, perm, None, None, Y, None, LSE, None, dYh, dQh, dKh, dVh, None, None, wsh)
+            sa.sa_rope(desc, dQh, dKh, table, dQh, dKh, inverse=1)
+        _, bu_ms = time_side(bwd_then_inverse_rope, max(5, args.steps // 20), 2)
+        wsr = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE), device=dev, dtype=torch.uint8)
+        _, bf_ms = time_side(lambda: sa.sa_bwd_rope(desc, Q, Kr, V, perm, table, Y, LSE, dYh, dQh, dKh, dVh, wsr,
+                                                    dk_unrotated=1), max(5, args.steps // 20), 2)
+        other.update({"sa_bwd_plus_inverse_rope_ms": bu_ms, "sa_bwd_rope_ms": bf_ms})
+        del dYh, dQh, dKh, dVh, wsh, wsr, Y2, Kr, table
         # the decoding step that follows this prefill (Sec. 4.2): one new token per sequence over the whole
         # 32K-row cache of the same heads; and a batch of 16 sequences with 8K-row caches
         for name, Bd, nd in (("decode_32k", 1, wl.n), ("decode_b16_8k", 16, 8192)):

@@ -82,7 +82,8 @@ typedef enum { SA_OP_FWD = 0, SA_OP_BWD = 1, SA_OP_GATED_FWD = 2, SA_OP_GATED_BW
                SA_OP_GATE_PROJ_BWD_SINGLE = 6, /* sa_gate_proj_bwd, single path   */
                SA_OP_DUAL_PATH_BWD = 7,        /* sa_dual_path_bwd                */
                SA_OP_SAMPLE_PERM = 8,          /* sa_sample_perm, O(n) path       */
-               SA_OP_DECODE = 9                /* sa_decode_fwd                   */
+               SA_OP_DECODE = 9,               /* sa_decode_fwd                   */
+               SA_OP_BWD_ROPE = 10             /* sa_bwd_rope                     */
 } sa_op;
 
 const char* sa_status_string(sa_status s);
@@ -175,6 +176,21 @@ sa_status sa_rope(const sa_desc* desc, const void* Q, const void* K, const float
  * for sa_rope.  perm = NULL: identity.  bf16 only (SA_ERR_UNSUPPORTED otherwise).  No workspace. */
 sa_status sa_fwd_rope(const sa_desc* desc, const void* Q, const void* K, const void* V, const int32_t* perm,
                       const float* rope_table, int32_t interleaved, void* Y, float* LSE, void* stream);
+
+/* The backward of sa_fwd_rope (App. B "Attention" item, App. C, Sec. 4.2: RoPE on original positions, then
+ * stochastic attention; the gradient of Eq. 1 over the visible set of Eq. 3 / App. B, and the transpose of the
+ * rotation of RoFormer Sec. 3.2.2).  Q arrives UNROTATED and K ROTATED, as for sa_fwd_rope; Y, LSE: what
+ * sa_fwd_rope returned; dY: gradient w.r.t. Y.  Each query row is rotated while the dQ kernel stages it (the
+ * rotated rows, rounded to bf16 as in the forward, are kept in the workspace for the dK/dV kernel, which
+ * streams them) and dQ is turned back in that kernel's epilogue: dQ is the gradient w.r.t. the UNROTATED Q.
+ * dk_unrotated = 1: dK is turned back in the dK/dV kernel's epilogue as well (gradient w.r.t. the unrotated K,
+ * what a caller that rotated K with sa_rope needs); 0: dK is the gradient w.r.t. the rotated K as given.
+ * dV as in sa_bwd.  All of dQ, dK, dV are overwritten.  bf16 only (SA_ERR_UNSUPPORTED otherwise).
+ * ws: sa_workspace_bytes(desc, SA_OP_BWD_ROPE) bytes of device memory (SA_ERR_WORKSPACE if smaller). */
+sa_status sa_bwd_rope(const sa_desc* desc, const void* Q, const void* K, const void* V, const int32_t* perm,
+                      const float* rope_table, int32_t interleaved, int32_t dk_unrotated, const void* Y,
+                      const float* LSE, const void* dY, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                      void* stream);
 
 /* Alg. 2 as printed (the dual-path layer between the Q/K/V and the output projections):
  *   Y_sa = StochasticAttn(Q,K,V; perm) [sa_fwd with `sa`],  Y_swa = SWA(Q,K,V) [sa_fwd with `swa`, identity],

@@ -19,11 +19,12 @@ SA_WIN_SYM_CIRCULAR, SA_WIN_SYM_LINEAR, SA_WIN_ONE_SIDED = 0, 1, 2
 SA_OP_FWD, SA_OP_BWD, SA_OP_GATED_FWD, SA_OP_GATED_BWD, SA_OP_CHECK_PERM = range(5)
 SA_OP_GATE_PROJ_BWD, SA_OP_GATE_PROJ_BWD_SINGLE, SA_OP_DUAL_PATH_BWD, SA_OP_SAMPLE_PERM = 5, 6, 7, 8
 SA_OP_DECODE = 9
+SA_OP_BWD_ROPE = 10
 
 EXPORTS = ("sa_status_string", "sa_workspace_bytes", "sa_check_perm", "sa_fwd", "swa_fwd",
            "gated_sa_swa_fwd", "sa_bwd", "sa_permuted_copy", "sa_gate_proj_fwd",
            "sa_gate_proj_bwd", "sa_sample_perm", "sa_dual_path_fwd", "sa_dual_path_bwd",
-           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_decode_fwd", "sa_decode_fwd_varlen",
+           "sa_rope_table", "sa_rope", "sa_fwd_rope", "sa_bwd_rope", "sa_decode_fwd", "sa_decode_fwd_varlen",
            "sa_decode_fwd_static")
 
 
@@ -72,6 +73,8 @@ def _load():
     lib.sa_rope_table.argtypes = [C.c_int32, C.c_int32, C.c_double, C.c_int32, vp, vp]
     lib.sa_fwd_rope.restype = C.c_int
     lib.sa_fwd_rope.argtypes = [dp, vp, vp, vp, ip, vp, C.c_int32, vp, vp, vp]
+    lib.sa_bwd_rope.restype = C.c_int
+    lib.sa_bwd_rope.argtypes = [dp, vp, vp, vp, ip, vp, C.c_int32, C.c_int32, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.sa_rope.restype = C.c_int
     lib.sa_rope.argtypes = [dp, vp, vp, vp, C.c_int32, C.c_int32, vp, vp, vp]
     lib.sa_decode_fwd.restype = C.c_int
@@ -174,6 +177,12 @@ def sa_dual_path_bwd(sa, swa, Q, K, V, perm, W_sa, W_swa, Y_sa, Y_swa, G_sa, G_s
 def sa_fwd_rope(desc, Q, K, V, perm, table, Y, LSE=None, interleaved=0):
     _check(_lib.sa_fwd_rope(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(table), interleaved,
                             _ptr(Y), _ptr(LSE), _stream()), "sa_fwd_rope")
+
+
+def sa_bwd_rope(desc, Q, K, V, perm, table, Y, LSE, dY, dQ, dK, dV, ws, interleaved=0, dk_unrotated=0):
+    _check(_lib.sa_bwd_rope(C.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(perm), _ptr(table), interleaved,
+                            dk_unrotated, _ptr(Y), _ptr(LSE), _ptr(dY), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws),
+                            0 if ws is None else ws.numel() * ws.element_size(), _stream()), "sa_bwd_rope")
 
 
 def sa_rope_table(n, d, base, pos0, table):

@@ -206,6 +206,8 @@ size_t sa_workspace_bytes(const sa_desc* c, int op) {
     case SA_OP_DUAL_PATH_BWD: return dual_bwd_workspace(c).total;
     case SA_OP_SAMPLE_PERM: return sa::sample_perm_workspace_bytes(c->perm_B * c->perm_H, c->n);
     case SA_OP_DECODE: return align256(sa::decode_workspace_bytes(c->B, c->Hq, c->Hkv, c->n, c->d));
+    case SA_OP_BWD_ROPE:  // D | the rotated Q rows
+      return bwd_workspace(c, false).total + align256((size_t)c->B * c->Hq * c->n * c->d * 2);
     default: return 0;
   }
 }
@@ -578,6 +580,45 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   b.Dsum = pr.D_a;
   b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = gated ? 1 : 0;
   return hip_status(run_bwd(sa_d, b, st));
+}
+
+sa_status sa_bwd_rope(const sa_desc* c, const void* Q, const void* K, const void* V, const int32_t* perm,
+                      const float* rope_table, int32_t interleaved, int32_t dk_unrotated, const void* Y,
+                      const float* LSE, const void* dY, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                      void* stream) {
+  sa_status s = validate_desc(c);
+  if (s != SA_OK) return s;
+  if (!Q || !K || !V || !Y || !LSE || !dY || !dQ || !dK || !dV || !rope_table) return SA_ERR_NULL;
+  if ((interleaved != 0 && interleaved != 1) || (dk_unrotated != 0 && dk_unrotated != 1)) return SA_ERR_SHAPE;
+  if (c->dtype != SA_BF16) return SA_ERR_UNSUPPORTED;
+  if (!aligned_to(16, {Q, K, V, Y, dY, dQ, dK, dV, ws}) || !aligned_to(4, {perm, LSE}) || !aligned_to(8, {rope_table}))
+    return SA_ERR_UNSUPPORTED;
+  if (!head_span_ok(c)) return SA_ERR_UNSUPPORTED;
+  const BwdWorkspace w = bwd_workspace(c, false);
+  if (!ws || ws_bytes < sa_workspace_bytes(c, SA_OP_BWD_ROPE)) return SA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  char* base = reinterpret_cast<char*>(ws);
+
+  sa::Prep pr = {};
+  pr.rows = c->B * c->Hq * c->n;
+  pr.d = c->d;
+  pr.bf16 = 1;
+  pr.dY = dY;
+  pr.Y_a = Y;
+  pr.D_a = reinterpret_cast<float*>(base + w.off_Da);
+  hipError_t e = sa::launch_bwd_prepare(pr, st);
+  if (e != hipSuccess) return hip_status(e);
+
+  Pass b = make_pass(c, Q, K, V, perm);
+  b.rope_table = rope_table;
+  b.rope_interleaved = interleaved;
+  b.rope_dk = dk_unrotated;
+  b.Q_rot = base + w.total;
+  b.dO = dY;
+  b.lse_in = LSE;
+  b.Dsum = pr.D_a;
+  b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = 0;
+  return hip_status(sa::launch_bwd_mfma_bf16(b, st));
 }
 
 }  // extern "C"

@@ -102,10 +102,13 @@ __device__ __forceinline__ void stationary_get(const bf16_t* stage, int lane, bf
 // lane moves (as stationary_src gave them), orig_mine for the lane's own row c32.  `accumulate`
 // first adds what the rows already hold (the other branch's gradient, stored as bf16) in fp32 and rounds
 // the sum: two roundings in all, one per branch.  The staging area is private to the wave.
+// trow != nullptr: the rows are first turned back by the angle of their position (the transpose of RoPE).
 template <class C, int D>
 __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage, bf16_t* out_head, const int* src,
-                                           int orig_mine, int s0, int n, int lane, int accumulate) {
+                                           int orig_mine, int s0, int n, int lane, int accumulate,
+                                           const float2* trow = nullptr, int interleaved = 0) {
   const int g2 = lane >> 5, c32 = lane & 31;
+  if (trow) rope_transpose_accumulators<D>(acc, trow, g2, interleaved);
   const bf16_t* mine = out_head + (size_t)orig_mine * D;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
@@ -238,6 +241,17 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_d
     wave_lds_sync();
     stationary_get<C, D>(stage, lane, gf);
   }
+  const float2* rope_row = p.rope_table ? reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_q * (D / 2) : nullptr;
+  if (rope_row) {
+    // Q arrives unrotated: RoPE on the query's original position (App. B, App. C; Sec. 4.2), as in the forward;
+    // the rotated rows are left for the dK/dV kernel
+    rope_row_fragments<D>(qf, rope_row, g2, p.rope_interleaved);
+    if (s < n) {
+      bf16_t* qrow = reinterpret_cast<bf16_t*>(p.Q_rot) + (head_row0 + orig_q) * D;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) *reinterpret_cast<bf16x8*>(qrow + 16 * kk + 8 * g2) = qf[kk];
+    }
+  }
   const float lse2 = p.lse_in[head_row0 + orig_q] * kLog2e;
   const float Dq = p.Dsum[head_row0 + orig_q];
 
@@ -366,7 +380,7 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_d
   __syncthreads();
   bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::STR;
   store_rows<C, D>(dqacc, p.scale, stage, reinterpret_cast<bf16_t*>(p.dQ) + head_row0 * D, st_src, orig_q, s_w0, n, lane,
-                   p.accumulate);
+                   p.accumulate, rope_row, p.rope_interleaved);
 }
 
 // --------------------------------------------------------------------------------------- dK, dV
@@ -709,7 +723,8 @@ __global__ __launch_bounds__(NT, D == 128 ? DKV128_WAVES : DKV64_WAVES) void bwd
   __syncthreads();
   bf16_t* dKh = reinterpret_cast<bf16_t*>(p.dK) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
   bf16_t* dVh = reinterpret_cast<bf16_t*>(p.dV) + ((size_t)b * p.Hkv + hk) * n * (size_t)D;
-  store_rows<C, D>(dkacc, p.scale, stage, dKh, st_src, orig_k, t_w0, n, lane, p.accumulate);
+  const float2* rope_row = p.rope_dk ? reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_k * (D / 2) : nullptr;
+  store_rows<C, D>(dkacc, p.scale, stage, dKh, st_src, orig_k, t_w0, n, lane, p.accumulate, rope_row, p.rope_interleaved);
   store_rows<C, D>(dvacc, 1.f, stage, dVh, st_src, orig_k, t_w0, n, lane, p.accumulate);
 }
 
@@ -763,11 +778,15 @@ hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (!p.dO || !p.lse_in || !p.Dsum || !p.dQ || !p.dK || !p.dV) return hipErrorInvalidValue;
   if (!(p.d == 64 || p.d == 128)) return hipErrorNotSupported;
   if ((long)p.n * p.d * 2 >= (1L << 31)) return hipErrorNotSupported;  // 32-bit row offsets inside a head
+  if (p.rope_dk && !p.rope_table) return hipErrorInvalidValue;
+  if (p.rope_table && !p.Q_rot) return hipErrorInvalidValue;
   hipError_t e = p.d == 64 ? launch_dq_t<64>(p, st) : launch_dq_t<128>(p, st);
   if (e != hipSuccess) return e;
+  Pass kv = p;
+  if (p.rope_table) kv.Q = p.Q_rot;  // the dQ kernel has left the rotated rows there
   if (p.perm && p.perm_H != 1 && p.g > 1) {
     // every query head of a group has its own slot order: one pass per head, summed in place
-    Pass q = p;
+    Pass q = kv;
     for (int hg = 0; hg < p.g; ++hg) {
       q.hq_only = hg;
       q.accumulate = (hg == 0) ? p.accumulate : 1;
@@ -776,7 +795,7 @@ hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st) {
     }
     return hipSuccess;
   }
-  return p.d == 64 ? launch_dkv_t<64>(p, st) : launch_dkv_t<128>(p, st);
+  return p.d == 64 ? launch_dkv_t<64>(kv, st) : launch_dkv_t<128>(kv, st);
 }
 
 }  // namespace sa

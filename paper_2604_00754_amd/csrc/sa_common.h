@@ -26,10 +26,14 @@ struct Pass {
   Window win;
   int causal;
   float scale;          // softmax scale (Eq. 1)
-  // bf16 forward only: rotate the Q rows on their original positions while they are staged (RoPE table
-  // [n][d/2][2] of sa_rope_table; nullptr = Q arrives rotated).  K always arrives rotated.
+  // bf16 only: rotate the Q rows on their original positions while they are staged (RoPE table [n][d/2][2]
+  // of sa_rope_table; nullptr = Q arrives rotated).  K always arrives rotated.  In the backward the dQ kernel
+  // does the same, leaves the rotated rows in Q_rot for the dK/dV kernel (which streams them) and turns dQ back
+  // in its epilogue; rope_dk: the dK/dV kernel turns dK back as well (gradient w.r.t. the unrotated K).
   const float* rope_table;
   int rope_interleaved;
+  void* Q_rot;
+  int rope_dk;
   // forward outputs
   void* Y;              // branch output rows, may be nullptr when only the gated sum is wanted
   float* LSE;           // may be nullptr

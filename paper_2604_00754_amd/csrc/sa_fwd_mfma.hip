@@ -210,47 +210,9 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk)
     qf[kk] = *reinterpret_cast<const bf16x8*>(Qs + c32 * C::QSTR + 16 * kk + 8 * g2);
-  if (p.rope_table) {
-    // RoPE on the query's ORIGINAL position (App. B, App. C; Sec. 4.2), applied to the operand fragments: a lane
-    // holds elements 16kk + 8*g2 .. +7 of its row for every kk, so both members of a pair are its own --
-    // (x[i], x[i + D/2]) sit in fragments kk and kk + D/32, (x[2i], x[2i+1]) next to each other.
-    const float2* trow = reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_q * (D / 2);
-    if (!p.rope_interleaved) {
-#pragma unroll
-      for (int kk = 0; kk < D / 32; ++kk) {
-        const float4* tp = reinterpret_cast<const float4*>(trow + 16 * kk + 8 * g2);
-        const u32x4 a = __builtin_bit_cast(u32x4, qf[kk]), b = __builtin_bit_cast(u32x4, qf[kk + D / 32]);
-        u32x4 ra, rb;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {  // dword m = elements 2m, 2m+1 of the fragment
-          const float4 t = tp[m];      // (cos, sin) of pairs 2m and 2m+1
-          const float a0 = bf16lo(a[m]), a1 = bf16hi(a[m]), b0 = bf16lo(b[m]), b1 = bf16hi(b[m]);
-          ra[m] = pack_bf16(a0 * t.x - b0 * t.y, a1 * t.z - b1 * t.w);
-          rb[m] = pack_bf16(a0 * t.y + b0 * t.x, a1 * t.w + b1 * t.z);
-        }
-        qf[kk] = __builtin_bit_cast(bf16x8, ra);
-        qf[kk + D / 32] = __builtin_bit_cast(bf16x8, rb);
-      }
-    } else {
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const float4* tp = reinterpret_cast<const float4*>(trow + 8 * kk + 4 * g2);
-        const u32x4 a = __builtin_bit_cast(u32x4, qf[kk]);
-        u32x4 ra;
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {  // dwords 2m, 2m+1 = pairs 2m, 2m+1 of the fragment
-          const float4 t = tp[m];
-          const float x0 = bf16lo(a[2 * m]), y0 = bf16hi(a[2 * m]);
-          const float x1 = bf16lo(a[2 * m + 1]), y1 = bf16hi(a[2 * m + 1]);
-          ra[2 * m] = pack_bf16(x0 * t.x - y0 * t.y, x0 * t.y + y0 * t.x);
-          ra[2 * m + 1] = pack_bf16(x1 * t.z - y1 * t.w, x1 * t.w + y1 * t.z);
-        }
-        qf[kk] = __builtin_bit_cast(bf16x8, ra);
-      }
-    }
-  }
-
-
+  // RoPE on the query's ORIGINAL position (App. B, App. C; Sec. 4.2), applied to the operand fragments
+  if (p.rope_table)
+    rope_row_fragments<D>(qf, reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_q * (D / 2), g2, p.rope_interleaved);
 
   // ---- per-lane element offsets of the operand reads inside a swizzled tile (without the block's rows)
   int koff[D / 16], voff[D / 32][2];

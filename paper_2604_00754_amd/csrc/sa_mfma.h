@@ -102,6 +102,83 @@ __device__ __forceinline__ bf16x8 lds_read_transposed_swz(const bf16_t* rows16, 
   return __builtin_bit_cast(bf16x8, a);
 }
 
+// RoPE (RoFormer Sec. 3.2.2) of one row held as MFMA operand fragments: lane group g2 holds elements
+// 16kk + 8*g2 .. +7 of the row in f[kk], so both members of a pair are the lane's own -- (x[i], x[i + D/2]) sit
+// in fragments kk and kk + D/32, (x[2i], x[2i+1]) next to each other.  trow: the (cos, sin) of the row's
+// position, D/2 pairs.  The rotated values are rounded to bf16.
+template <int D>
+__device__ __forceinline__ void rope_row_fragments(bf16x8* f, const float2* trow, int g2, int interleaved) {
+  if (!interleaved) {
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+      const float4* tp = reinterpret_cast<const float4*>(trow + 16 * kk + 8 * g2);
+      const u32x4 a = __builtin_bit_cast(u32x4, f[kk]), b = __builtin_bit_cast(u32x4, f[kk + D / 32]);
+      u32x4 ra, rb;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {  // dword m = elements 2m, 2m+1 of the fragment
+        const float4 t = tp[m];      // (cos, sin) of pairs 2m and 2m+1
+        const float a0 = bf16lo(a[m]), a1 = bf16hi(a[m]), b0 = bf16lo(b[m]), b1 = bf16hi(b[m]);
+        ra[m] = pack_bf16(a0 * t.x - b0 * t.y, a1 * t.z - b1 * t.w);
+        rb[m] = pack_bf16(a0 * t.y + b0 * t.x, a1 * t.w + b1 * t.z);
+      }
+      f[kk] = __builtin_bit_cast(bf16x8, ra);
+      f[kk + D / 32] = __builtin_bit_cast(bf16x8, rb);
+    }
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const float4* tp = reinterpret_cast<const float4*>(trow + 8 * kk + 4 * g2);
+      const u32x4 a = __builtin_bit_cast(u32x4, f[kk]);
+      u32x4 ra;
+#pragma unroll
+      for (int m = 0; m < 2; ++m) {  // dwords 2m, 2m+1 = pairs 2m, 2m+1 of the fragment
+        const float4 t = tp[m];
+        const float x0 = bf16lo(a[2 * m]), y0 = bf16hi(a[2 * m]);
+        const float x1 = bf16lo(a[2 * m + 1]), y1 = bf16hi(a[2 * m + 1]);
+        ra[2 * m] = pack_bf16(x0 * t.x - y0 * t.y, x0 * t.y + y0 * t.x);
+        ra[2 * m + 1] = pack_bf16(x1 * t.z - y1 * t.w, x1 * t.w + y1 * t.z);
+      }
+      f[kk] = __builtin_bit_cast(bf16x8, ra);
+    }
+  }
+}
+
+// The transpose of that rotation (turn by the negative angle: the backward of RoPE) on a row held as transposed
+// accumulators: accumulator 4*mq + x of block db of lane group g2 is element 32 db + 8 mq + 4 g2 + x of the
+// lane's row, so again both members of a pair are the lane's own -- elements i and i + D/2 in blocks db and
+// db + D/64, elements 2i and 2i+1 in accumulators x = 0, 1 and 2, 3.  In fp32, in place.
+template <int D>
+__device__ __forceinline__ void rope_transpose_accumulators(f32x16* acc, const float2* trow, int g2, int interleaved) {
+  if (!interleaved) {
+#pragma unroll
+    for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        const float4* tp = reinterpret_cast<const float4*>(trow + 32 * db + 8 * mq + 4 * g2);
+        const float4 t01 = tp[0], t23 = tp[1];  // (cos, sin) of pairs x = 0, 1 and x = 2, 3
+        const float c[4] = {t01.x, t01.z, t23.x, t23.z}, sn[4] = {t01.y, t01.w, t23.y, t23.w};
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const float a = acc[db][4 * mq + x], b = acc[db + D / 64][4 * mq + x];
+          acc[db][4 * mq + x] = a * c[x] + b * sn[x];
+          acc[db + D / 64][4 * mq + x] = b * c[x] - a * sn[x];
+        }
+      }
+  } else {
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int mq = 0; mq < 4; ++mq) {
+        const float4 t = *reinterpret_cast<const float4*>(trow + 16 * db + 4 * mq + 2 * g2);  // pairs of x = 0,1 and 2,3
+        const float a0 = acc[db][4 * mq + 0], b0 = acc[db][4 * mq + 1], a1 = acc[db][4 * mq + 2], b1 = acc[db][4 * mq + 3];
+        acc[db][4 * mq + 0] = a0 * t.x + b0 * t.y;
+        acc[db][4 * mq + 1] = b0 * t.x - a0 * t.y;
+        acc[db][4 * mq + 2] = a1 * t.z + b1 * t.w;
+        acc[db][4 * mq + 3] = b1 * t.z - a1 * t.w;
+      }
+  }
+}
+
 // Pack accumulators 8c..8c+7 of a lane as a bf16 B operand.
 __device__ __forceinline__ bf16x8 pack_b_operand(const float* v8) {
   u32x4 w;

@@ -203,3 +203,29 @@ def test_static_decode_refuses_what_its_buffer_cannot_hold():
     assert lib.sa_decode_fwd_static(C.byref(fits), None, FAKE, FAKE, 16, FAKE, None, None) == sa.SA_ERR_NULL
     assert lib.sa_decode_fwd_static(C.byref(fits), FAKE, FAKE, FAKE, 0, FAKE, None, None) == sa.SA_ERR_SHAPE
     assert lib.sa_decode_fwd_static(None, FAKE, FAKE, FAKE, 1, FAKE, None, None) == sa.SA_ERR_NULL
+
+
+def test_bwd_rope_arguments():
+    """sa_bwd_rope validates on the host: nulls, flags, dtype, alignment, the 2 GiB head limit, the workspace
+    (the plain backward's plus the rotated query rows)."""
+    lib = sa.raw()
+    d = good()
+    need = sa.sa_workspace_bytes(d, sa.SA_OP_BWD_ROPE)
+    assert need >= sa.sa_workspace_bytes(d, sa.SA_OP_BWD) + d.B * d.Hq * d.n * d.d * 2
+
+    def call(desc=d, table=FAKE, inter=0, dku=0, dv=FAKE, ws=FAKE, nb=need):
+        return lib.sa_bwd_rope(C.byref(desc), FAKE, FAKE, FAKE, None, table, inter, dku, FAKE, FAKE, FAKE, FAKE, FAKE,
+                               dv, ws, nb, None)
+
+    assert call(table=None) == sa.SA_ERR_NULL
+    assert call(dv=None) == sa.SA_ERR_NULL
+    assert call(inter=2) == sa.SA_ERR_SHAPE
+    assert call(dku=-1) == sa.SA_ERR_SHAPE
+    assert call(dv=C.c_void_p(4096 + 8)) == sa.SA_ERR_UNSUPPORTED
+    assert call(table=C.c_void_p(4096 + 4)) == sa.SA_ERR_UNSUPPORTED
+    assert call(ws=None) == sa.SA_ERR_WORKSPACE
+    assert call(nb=need - 1) == sa.SA_ERR_WORKSPACE
+    f32 = sa.make_desc(2, 8, 2, 1000, 128, 256, dtype=sa.SA_F32)
+    assert call(desc=f32) == sa.SA_ERR_UNSUPPORTED
+    big = sa.make_desc(1, 1, 1, 1 << 23, 128, 512)
+    assert call(desc=big, nb=1 << 40) == sa.SA_ERR_UNSUPPORTED

@@ -175,3 +175,74 @@ def test_fwd_rope_rejects_unsupported():
     with pytest.raises(sa.SaError) as e:
         sa.sa_fwd_rope(sa.make_desc(1, 1, 1, 8, 64, 4), xb, xb, xb, None, None, torch.empty_like(xb))
     assert e.value.status == sa.SA_ERR_NULL
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("interleaved", [0, 1])
+@pytest.mark.parametrize("dk_unrotated", [0, 1])
+def test_backward_with_fused_rotations(d, interleaved, dk_unrotated):
+    """sa_bwd_rope (Q rotated while the dQ kernel stages it, dQ -- and on request dK -- turned back in the
+    epilogues) against rope -> analytic gradient -> rope^T of the oracle in fp64."""
+    from oracle import binding as orc
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    B, Hq, Hkv, n, w = 2, 4, 2, 700, 128
+    # shared permutation; one permutation per query head (one dK/dV pass per head of a group, summed in place);
+    # identity order with the one-sided window (the SWA branch)
+    for identity, window, perm_H in ((False, 0, 1), (False, 0, Hq), (True, 2, 1)):
+        print(f"case bwd_rope B{B} Hq{Hq} Hkv{Hkv} n{n} d{d} w{w} interleaved={interleaved} dk_unrotated={dk_unrotated} "
+              f"identity={identity} perm_H={perm_H}", flush=True)
+        wl, x = U.make_case(B, Hq, Hkv, n, d, w, "bf16", 1, perm_H, seed=300 + d + interleaved, grads=True,
+                            identity=identity)
+        Q, K, V, dY = (U.to_dev(x[k], "bf16") for k in ("Q", "K", "V", "dY"))
+        kw = dict(base=1e4, pos0=0, interleaved=bool(interleaved))
+        # as in the forward, the rotated rows are bf16 values on both sides
+        rq = synth.round_to_bf16(R.rope(U.to_np64(Q), **kw).astype(np.float32))
+        rk = synth.round_to_bf16(R.rope(U.to_np64(K), **kw).astype(np.float32))
+        oc = U.orc_desc(wl, window, 1)
+        dq, dk, dv = orc.sa_bwd(oc, rq, rk, U.to_np64(V), x["perm"], U.to_np64(dY))
+        dq = R.rope(dq, inverse=True, **kw)
+        if dk_unrotated:
+            dk = R.rope(dk, inverse=True, **kw)
+        perm = None if identity else torch.from_numpy(x["perm"]).to(U.DEV)
+        desc = U.sa_desc(wl, window, 1)
+        table = gpu_table(n, d, 1e4, 0)
+        Kr = torch.empty_like(K)
+        sa.sa_rope(desc, None, K, table, None, Kr, interleaved=interleaved)
+        Y = torch.empty_like(Q)
+        L = torch.empty((B, Hq, n), device=U.DEV)
+        sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, L, interleaved=interleaved)
+        dQ, dK, dV = (torch.full_like(t, float("nan")) for t in (Q, K, V))
+        ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE),), 255, device=U.DEV, dtype=torch.uint8)
+        Q0 = Q.clone()
+        sa.sa_bwd_rope(desc, Q, Kr, V, perm, table, Y, L, dY, dQ, dK, dV, ws, interleaved=interleaved,
+                       dk_unrotated=dk_unrotated)
+        torch.cuda.synchronize()
+        assert torch.equal(Q, Q0)     # the rotated rows go to the workspace, not over the input
+        for name, got, ref in (("dQ", dQ, dq), ("dK", dK, dk), ("dV", dV, dv)):
+            U.assert_close(U.to_np64(got), ref, "bf16", name, scale_abs=max(1.0, float(np.abs(ref).max())))
+
+
+def test_bwd_rope_rejects_unsupported():
+    from paper_2604_00754_amd import binding as sa
+    t = torch.zeros((8, 32, 2), device=U.DEV)
+    xb = torch.zeros((1, 1, 8, 64), device=U.DEV, dtype=torch.bfloat16)
+    L = torch.zeros((1, 1, 8), device=U.DEV)
+    desc = sa.make_desc(1, 1, 1, 8, 64, 4)
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE), device=U.DEV, dtype=torch.uint8)
+    out = [torch.empty_like(xb) for _ in range(3)]
+    with pytest.raises(sa.SaError) as e:   # no table
+        sa.sa_bwd_rope(desc, xb, xb, xb, None, None, xb, L, xb, *out, ws)
+    assert e.value.status == sa.SA_ERR_NULL
+    with pytest.raises(sa.SaError) as e:   # workspace of the plain backward: too small for the rotated rows
+        sa.sa_bwd_rope(desc, xb, xb, xb, None, t, xb, L, xb, *out, ws[:sa.sa_workspace_bytes(desc, sa.SA_OP_BWD)])
+    assert e.value.status == sa.SA_ERR_WORKSPACE
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_bwd_rope(desc, xb, xb, xb, None, t, xb, L, xb, *out, ws, dk_unrotated=2)
+    assert e.value.status == sa.SA_ERR_SHAPE
+    xf = xb.float()
+    with pytest.raises(sa.SaError) as e:
+        sa.sa_bwd_rope(sa.make_desc(1, 1, 1, 8, 64, 4, dtype=sa.SA_F32), xf, xf, xf, None, t, xf, L, xf,
+                       *[torch.empty_like(xf) for _ in range(3)], ws)
+    assert e.value.status == sa.SA_ERR_UNSUPPORTED
