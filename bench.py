@@ -22,9 +22,34 @@ sys.path.insert(0, ROOT)
 METRIC = "SA fwd(+bwd) tokens/s and TFLOP/s (% bf16 MFMA peak) at n=32K, w=512"
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM bytes per sa_fwd launch at the headline shape, from two rocprofv3 --pmc runs (FETCH_SIZE scaled
-# by 2.000, WRITE_SIZE by 1.000 against a 1 GiB copy); see profiles/fwd_mfma_bf16_d128_qwen3_8b_prefill_32k.md
-MEASURED_TRAFFIC_BYTES = 396600 * 1024 + 303800 * 1024
+CSRC = os.path.join(ROOT, "paper_2604_00754_amd", "csrc")
+
+
+def measured_traffic(op, workload):
+    """HBM bytes per call of `op` on `workload` as the hardware counters saw them: taken from the `traffic-record:`
+    line of a summary under profiles/ (two rocprofv3 --pmc runs, FETCH_SIZE and WRITE_SIZE, each scaled by what the
+    same counter reads for a 1 GiB copy).  The record names the kernel sources it was taken with and their
+    SHA-256; if the sources in this tree differ, the figure belongs to other kernels and None is returned."""
+    import glob
+    import hashlib
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            if not line.startswith("traffic-record:"):
+                continue
+            rec = dict(kv.split("=", 1) for kv in line.split()[1:])
+            if rec.get("op") != op or rec.get("workload") != workload:
+                continue
+            h = hashlib.sha256()
+            for name in rec["sources"].split(","):
+                with open(os.path.join(CSRC, name), "rb") as f:
+                    h.update(f.read())
+            if h.hexdigest() != rec["sha256"]:
+                return None, f"{os.path.basename(path)}: kernel sources changed since the counters were read"
+            nbytes = (float(rec["fetch_kib"]) * float(rec["fetch_scale"]) +
+                      float(rec["write_kib"]) * float(rec["write_scale"])) * 1024.0
+            return nbytes, f"{os.path.basename(path)} (commit {rec.get('commit', '?')})"
+    return None, "no counter run on record for this call"
 
 
 def band_slots(n, w, window):
@@ -199,6 +224,51 @@ def long_prefill_ops(sa, synth, dev, reps):
         "swa_fwd_ms": t_swa, "swa_fwd_tokens_per_s": wl.B * wl.n / (t_swa * 1e-3)}}
 
 
+def backward_setup(sa, synth, dev, name):
+    """Tensors and the call for sa_bwd (ungated, one permutation shared by the heads) on a named workload."""
+    wl = synth.WORKLOADS[name]
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.BASE_SEED + 3)
+    rn = lambda shape: torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+    Q, dY = rn((wl.B, wl.Hq, wl.n, wl.d)), rn((wl.B, wl.Hq, wl.n, wl.d))
+    K, V = rn((wl.B, wl.Hkv, wl.n, wl.d)), rn((wl.B, wl.Hkv, wl.n, wl.d))
+    perm = torch.from_numpy(synth.permutations(1, 1, wl.n)).to(dev)
+    desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+    Y, dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    L = torch.empty((wl.B, wl.Hq, wl.n), device=dev, dtype=torch.float32)
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=dev, dtype=torch.uint8)
+    sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    keep = (Q, K, V, dY, perm, Y, dQ, dK, dV, L, ws)
+
+    def call():
+        sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    return wl, call, keep
+
+
+def backward_roofline(sa, synth, dev, steps, warmup):
+    """The second half of the metric: sa_bwd (row-sum pass, dQ kernel, dK/dV kernel) on the pre-training
+    shape B=4, H=16, n=8192, d=64, w=256, against both roofs.  Algorithmic flop: 5 contractions over the window
+    band, 10 n W d per (b, h); algorithmic bytes: Q, K, V, Y, dY, LSE and the index tensor in, dQ, dK, dV out."""
+    wl, call, keep = backward_setup(sa, synth, dev, "pretrain_fwdbwd_8k")
+    _, mean_ms = time_op(call, steps, warmup)
+    samples = list(time_op.last_samples_ms)
+    W = band_slots(wl.n, wl.w, 0)
+    flop = 10.0 * wl.n * W * wl.d * wl.B * wl.Hq
+    e = 2
+    nbytes = wl.B * wl.n * wl.d * e * (5 * wl.Hq + 3 * wl.Hkv) + wl.B * wl.Hq * wl.n * 4 + wl.n * 4
+    tflops, gbs = flop / (mean_ms * 1e-3) / 1e12, nbytes / (mean_ms * 1e-3) / 1e9
+    traffic, source = measured_traffic("sa_bwd", "pretrain_fwdbwd_8k")
+    return {"op": "sa_bwd", "workload": "pretrain_fwdbwd_8k", "shape": "B4 H16 n8192 d64 w256 bf16",
+            "kernels": ["bwd_prepare_kernel", "bwd_dq_mfma_bf16_kernel<64, 2>", "bwd_dkv_mfma_bf16_kernel<64, 2>"],
+            "dominant_kernel": "bwd_dkv_mfma_bf16_kernel<64, 2>",
+            "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+            "algorithmic_bytes": nbytes, "traffic": traffic, "traffic_source": source,
+            "mfma": {"achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
+                     "algorithmic_flop": flop},
+            "avg_call_ms": mean_ms, "median_call_ms": float(np.median(samples)), "min_call_ms": float(np.min(samples)),
+            "note": "one sa_bwd call = three kernels; the nearer roof at this shape is HBM (frac), the MFMA figure beside it"}
+
+
 def table3_sweep(sa, synth, dev):
     """Sec. 4.3 / Table 3 on this GPU: attention forward + backward in isolation, B=16, H=16, d=64,
     w=256, bf16, n = 2K ... 32K: single-path SA, plain causal SWA, gated SA+SWA, and full causal
@@ -243,6 +313,40 @@ def table3_sweep(sa, synth, dev):
     return {"table3_sweep": {"shape": "B16 H16 d64 w256 bf16, attention forward+backward", "rows": out}}
 
 
+def profile_side_op(sa, synth, dev, args):
+    """One entry point other than the headline step, called --steps times: for kernel traces and counter runs."""
+    copy_src = copy_dst = None
+    if args.calibrate_copy:
+        copy_src = torch.zeros(256 * 1024 * 1024, device=dev, dtype=torch.float32)  # 1 GiB
+        copy_dst = torch.empty_like(copy_src)
+    if args.profile_op == "gated_fwd":
+        wl = synth.WORKLOADS["pretrain_fwdbwd_8k"]
+        g = torch.Generator(device=dev)
+        g.manual_seed(synth.BASE_SEED + 4)
+        rn = lambda shape, dt=torch.bfloat16: torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(dt)
+        Q, K, V = (rn((wl.B, wl.Hq, wl.n, wl.d)) for _ in range(3))
+        ga, gl = rn((wl.B, wl.Hq, wl.n), torch.float32), rn((wl.B, wl.Hq, wl.n), torch.float32)
+        perm = torch.from_numpy(synth.permutations(1, 1, wl.n)).to(dev)
+        dsa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+        dswa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16, 0.0, 1, 1)
+        Y, Ysa, Yswa = (torch.empty_like(Q) for _ in range(3))
+        Lsa = torch.empty((wl.B, wl.Hq, wl.n), device=dev, dtype=torch.float32)
+        Lswa = torch.empty_like(Lsa)
+        wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=dev, dtype=torch.uint8)
+        call = lambda: sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
+    else:
+        wl, call, keep = backward_setup(sa, synth, dev, "pretrain_fwdbwd_8k" if args.profile_op == "sa_bwd"
+                                        else "qwen3_8b_prefill_32k")
+
+    def step():
+        if copy_src is not None:
+            copy_dst.copy_(copy_src)
+        call()
+    _, mean_ms = time_op(step, args.steps, args.warmup)
+    return {"op": args.profile_op, "workload": wl.name, "steps": args.steps, "warmup": args.warmup,
+            "avg_step_ms": mean_ms, "calibrate_copy": bool(args.calibrate_copy)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -254,6 +358,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy before and between steps (a known-size kernel "
                          "for scaling the FETCH_SIZE / WRITE_SIZE counters; it also empties the caches)")
+    ap.add_argument("--profile-op", choices=["sa_fwd", "sa_bwd", "sa_bwd_headline", "gated_fwd"], default=None,
+                    help="profiling runs: call this entry point --steps times (after --warmup) and print a short JSON "
+                         "line; sa_fwd = the headline step, sa_bwd / gated_fwd = the pre-training shape B4 H16 n8192 "
+                         "d64 w256, sa_bwd_headline = the backward at the headline shape; honours --calibrate-copy")
     ap.add_argument("--table3", action="store_true",
                     help="instead of the headline step, run the sequence-length sweep of Sec. 4.3 / Table 3 "
                          "(SA, SWA, gated, full attention; forward + backward) and print it as one JSON line")
@@ -272,6 +380,9 @@ def main():
     dev = "cuda:0"
     if args.table3:
         print(json.dumps(table3_sweep(sa, synth, dev)))
+        return
+    if args.profile_op in ("sa_bwd", "sa_bwd_headline", "gated_fwd"):
+        print(json.dumps(profile_side_op(sa, synth, dev, args)))
         return
     wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
     g = torch.Generator(device=dev)
@@ -306,9 +417,11 @@ def main():
     e = 2
     alg_bytes = wl.B * wl.n * (wl.Hq * 2 * wl.d * e + wl.Hkv * 2 * wl.d * e + wl.Hq * 4) + wl.n * 4
     tflops = band_flop / (launch_ms * 1e-3) / 1e12
+    traffic, traffic_source = measured_traffic("sa_fwd", "qwen3_8b_prefill_32k")
     roofline = {"bound": "mfma", "kernel": "fwd_mfma_bf16_kernel<128, true, 2, false>", "achieved": tflops,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
+                "traffic": traffic, "traffic_source": traffic_source,
+                "algorithmic_flop": band_flop, "avg_launch_ms": launch_ms,
                 "median_launch_ms": float(np.median(launch_samples)), "min_launch_ms": float(np.min(launch_samples)),
                 "executed_flop": executed_flop(wl.n, wl.w, wl.d, wl.B, wl.Hq, BM=128 // heads_per_workgroup(wl),
                                                BN=32 if wl.d == 128 else 64),
@@ -436,6 +549,9 @@ def main():
                       "causal_orig": 1, "perm": "one per layer, shared by heads"},
            "tflops_band": tflops, "pct_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
            "roofline": roofline, "roofline_hbm": roofline_hbm, "other_ops": other}
+    if not args.only_step:
+        # the backward half of the metric, on the configuration the paper trains at
+        out["roofline_bwd"] = backward_roofline(sa, synth, dev, max(10, args.steps), max(3, args.warmup))
 
     if not args.no_cpu_baseline and not args.only_step:
         base, rows, Yr = cpu_baseline(wl, Q, K, V, perm, args.cpu_rows_per_head)
@@ -445,6 +561,8 @@ def main():
         base["gpu_vs_oracle_on_sample"] = {"max_abs": float(np.abs(diff).max()),
                                            "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(Yr))}
         out["cpu_baseline"] = base
+        # the same launch priced by the pairs the mask leaves visible (counted by the oracle): about half the band
+        out["tflops_visible_pairs"] = base["useful_flop"] / (launch_ms * 1e-3) / 1e12
     print(json.dumps(out))
 
 
