@@ -158,6 +158,63 @@ def test_qwen3_8b_prefill_32k_fused_query_rotation_sampled_rows():
     print(f"  {rows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e} lse {la:.1e}", flush=True)
 
 
+def test_qwen3_8b_prefill_32k_backward_with_fused_rotations_sampled_rows():
+    """sa_bwd_rope at the headline shape with the Qwen3 base 10^6 and dK turned back, the call bench.py times as
+    `sa_bwd_rope`: dQ on sampled query rows, dK and dV on sampled key rows, against rope -> row-wise fp64 gradients
+    -> rope^T of the oracle (the inverse rotation of a row needs that row only)."""
+    from oracle import binding as orc
+    from oracle import rope as R
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
+    print("case fullsize bwd_rope qwen3_8b_prefill_32k", flush=True)
+    B, Hq, Hkv, n, d = wl.B, wl.Hq, wl.Hkv, wl.n, wl.d
+    Q = gpu_normal((B, Hq, n, d), 1)
+    K = gpu_normal((B, Hkv, n, d), 2)
+    V = gpu_normal((B, Hkv, n, d), 3)
+    dY = gpu_normal((B, Hq, n, d), 4)
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    desc = U.sa_desc(wl, CIRC, 1)
+    table = torch.empty((n, d // 2, 2), device=U.DEV, dtype=torch.float32)
+    sa.sa_rope_table(n, d, 1e6, 0, table)
+    Kr = torch.empty_like(K)
+    sa.sa_rope(desc, None, K, table, None, Kr)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd_rope(desc, Q, Kr, V, perm, table, Y, L)
+    dQ = torch.full_like(Q, float("nan"))
+    dK, dV = torch.full_like(K, float("nan")), torch.full_like(K, float("nan"))
+    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE), device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd_rope(desc, Q, Kr, V, perm, table, Y, L, dY, dQ, dK, dV, ws, dk_unrotated=1)
+    torch.cuda.synchronize()
+    for t in (dQ, dK, dV):
+        assert torch.isfinite(t.float()).all().item()
+    rq = synth.round_to_bf16(R.rope(host64(Q), base=1e6).astype(np.float32)).astype(np.float64)
+    rk = synth.round_to_bf16(R.rope(host64(K), base=1e6).astype(np.float32)).astype(np.float64)
+    V64, dY64 = host64(V), host64(dY)
+    od = U.orc_desc(wl, CIRC, 1)
+    ang = R.angles(n, d, 1e6, 0)
+
+    def turn_back(rows_grad, positions):  # rope^T of single rows (split-halves pairing), each at its own position
+        c, sn = np.cos(ang[positions]), np.sin(ang[positions])
+        a, b = rows_grad[:, :d // 2], rows_grad[:, d // 2:]
+        return np.concatenate([a * c + b * sn, b * c - a * sn], axis=1)
+
+    scale = lambda r: max(1.0, float(np.abs(r).max()))
+    rows = np.concatenate([synth.sample_rows(B, Hq, n, 16, seed=31), edge_rows(perm_np, B, Hq, n)])
+    dQ_r = turn_back(orc.sa_bwd_dq_rows(od, rq, rk, V64, perm_np, dY64, rows), rows[:, 2])
+    ma, rl = U.assert_close(pick(dQ, rows), dQ_r, "bf16", "dQ rows (fused rotations)", scale_abs=scale(dQ_r))
+    print(f"  dQ: {rows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+    krows = np.concatenate([synth.sample_rows(B, Hkv, n, 8, seed=32), edge_rows(perm_np, B, Hkv, n)])
+    dK_r, dV_r = orc.sa_bwd_dkv_rows(od, rq, rk, V64, perm_np, dY64, krows)
+    dK_r = turn_back(dK_r, krows[:, 2])
+    ma, rl = U.assert_close(pick(dK, krows), dK_r, "bf16", "dK rows (fused rotations)", scale_abs=scale(dK_r))
+    print(f"  dK: {krows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+    ma, rl = U.assert_close(pick(dV, krows), dV_r, "bf16", "dV rows (fused rotations)", scale_abs=scale(dV_r))
+    print(f"  dV: {krows.shape[0]} rows max-abs {ma:.2e} rel-L2 {rl:.2e}", flush=True)
+
+
 def test_pretrain_fwdbwd_8k_gated_sampled_rows():
     """Fourth benchmark configuration: B=4, H=16, n=8192, d=64, w=256, gated SA+SWA forward and
     backward, one permutation per layer shared by the heads."""
