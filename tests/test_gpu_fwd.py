@@ -37,6 +37,13 @@ def run_fwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed
     U.assert_close(U.to_np64(Y), Yr, dtype, "Y")
     la = np.abs(U.to_np64(L) - Lr).max()
     assert la <= (4e-3 if dtype == "bf16" else 1e-5), f"LSE max-abs {la:.3e}"
+    if causal:
+        # the token at original position 0 sees itself only (Sec. 3.3: causal on original positions), whatever the
+        # window and wherever it sits in the permuted order: its output is its own V row, bit for bit -- one masked
+        # key that leaked with any weight would change it
+        g = Hq // Hkv
+        for hq in range(Hq):
+            assert torch.equal(Y[:, hq, 0, :], V[:, hq // g, 0, :]), f"head {hq}: row of original position 0"
 
 
 def test_tiny_f32_config():
