@@ -13,9 +13,12 @@
 // barrier per tile), and consumed by
 //   S^T = K Q^T          (v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in registers)
 //   mask: window on slot offsets, causal test on original positions (Sec. 3.3, App. B)
-//   online softmax (Eq. 1) -- in the S^T layout a lane holds one query column, so row statistics
-//   are lane-local up to one exchange with lane^32; the running maximum is only moved when a tile
-//   exceeds it by more than 2^8, which leaves the normalised result unchanged
+//   softmax (Eq. 1) -- in the S^T layout a lane holds one query column, so row statistics are lane-local
+//   up to one exchange with lane^32.  A workgroup first walks its band with the softmax reference fixed
+//   at zero (p = exp2(cs * s): no maximum, no rescaling; O and l carry the same reference, so O / l does
+//   not depend on it) and looks at the row sums at the end; only if one of them left the range that form
+//   holds in fp32 does it walk the band again in the online form, with a running maximum that is moved
+//   when a tile exceeds it by more than 2^8
 //   O^T += V^T P^T       (A = V^T gathered from the row-major V tile by transposing LDS reads,
 //                         ds_read_b64_tr_b16; B = P^T taken directly from the S^T accumulators)
 // The epilogue normalises, transposes through LDS and writes each row to its ORIGINAL position
@@ -155,18 +158,21 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
   for (int pass = 0; pass < NP; ++pass) src[pass] = orig_of(min(s_w0 + pass * C::WRPP + lane / C::CPR, n - 1));
   int* rowstash = reinterpret_cast<int*>(smem + C::RING_OFF + C::RING * BN * 6);  // original index of the workgroup's 128 rows
   int pk_reg = 0;
-  if (tid < BN) {
-    const int i0 = tile_row_orig(0), i1 = tile_row_orig(1), i2 = tile_row_orig(2);
-    pk_reg = tile_row_orig(3);
-    ring[0 * BN + tid] = i0;
-    ring[1 * BN + tid] = i1;
-    ring[2 * BN + tid] = i2;
-    if (CAUSAL == CAUSAL_I16) {
-      ring16[0 * BN + pos16] = (short)(i0 - 32768);
-      ring16[1 * BN + pos16] = (short)(i1 - 32768);
-      ring16[2 * BN + pos16] = (short)(i2 - 32768);
+  auto init_ring = [&]() {  // indices of tiles 0..2 -> ring, tile 3 -> register (the state the tile loop starts from)
+    if (tid < BN) {
+      const int i0 = tile_row_orig(0), i1 = tile_row_orig(1), i2 = tile_row_orig(2);
+      pk_reg = tile_row_orig(3);
+      ring[0 * BN + tid] = i0;
+      ring[1 * BN + tid] = i1;
+      ring[2 * BN + tid] = i2;
+      if (CAUSAL == CAUSAL_I16) {
+        ring16[0 * BN + pos16] = (short)(i0 - 32768);
+        ring16[1 * BN + pos16] = (short)(i1 - 32768);
+        ring16[2 * BN + pos16] = (short)(i2 - 32768);
+      }
     }
-  }
+  };
+  init_ring();
   if (chunk16 == 0) {
 #pragma unroll
     for (int pass = 0; pass < NP; ++pass) rowstash[wave * 32 + pass * C::WRPP + lane / C::CPR] = src[pass];
@@ -229,8 +235,9 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
     for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
 
   // one tile; BUF (0/1) is a compile-time constant so that all LDS addresses are immediates
-  auto do_tile = [&](const int tile, auto bufc) {
+  auto do_tile = [&](const int tile, auto bufc, auto fastc) {
     constexpr int buf = decltype(bufc)::value;
+    constexpr bool FAST = decltype(fastc)::value;
     // this wave's share of the tile has landed; after the barrier the whole tile is visible and everyone
     // is done with the other buffer (tile-1, Q staging)
     wait_all_loads();
@@ -322,8 +329,10 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
       }
     }
 
-    // ---- online softmax (Eq. 1) on the lane's query column, with a lazily updated reference maximum:
+    // ---- softmax (Eq. 1) on the lane's query column.  FAST: reference zero, nothing to do before the
+    // exponentials.  Otherwise the online form with a lazily updated reference maximum:
     // p = exp2(cs*(s - m_ref)) stays <= 2^8, and O and l carry the same reference, so O/l is unchanged
+    if (!FAST) {
     float mx = sacc[0][0];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb)
@@ -354,7 +363,8 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     }
-    const float mc = (m_ref == -INFINITY ? 0.f : m_ref) * cs;
+    }
+    const float mc = FAST ? 0.f : (m_ref == -INFINITY ? 0.f : m_ref) * cs;
     bf16x8 pf[NB][2];
 #pragma unroll
     for (int kb = 0; kb < NB; ++kb) {
@@ -384,14 +394,20 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
         pf[kb][0] = __builtin_bit_cast(bf16x8, w[0]);
         pf[kb][1] = __builtin_bit_cast(bf16x8, w[1]);
       } else {
-        float pe[16];
+        // the row sum is taken from the bf16 pairs that build O, as in the 16-bit mode: the weights O / l then sum
+        // to one exactly, and a row that sees a single key returns that key's V row bit for bit
+        const bf16x2 ones = {(bf16_t)1.f, (bf16_t)1.f};
+        u32x4 w[2];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          pe[i] = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], cs, -mc));
-          l_run += pe[i];
+        for (int e = 0; e < 8; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][2 * e], cs, -mc));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][2 * e + 1], cs, -mc));
+          const uint32_t pp = pack_bf16(p0, p1);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pp), ones, l_run, false);
+          w[e >> 2][e & 3] = pp;
         }
-        pf[kb][0] = pack_b_operand(pe);
-        pf[kb][1] = pack_b_operand(pe + 8);
+        pf[kb][0] = __builtin_bit_cast(bf16x8, w[0]);
+        pf[kb][1] = __builtin_bit_cast(bf16x8, w[1]);
       }
     }
 
@@ -408,13 +424,36 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
         }
     }
   };
-  for (int tile = 0; tile < ntiles; tile += 2) {
-    do_tile(tile, std::integral_constant<int, 0>{});
-    if (tile + 1 < ntiles) do_tile(tile + 1, std::integral_constant<int, 1>{});
+  auto run_band = [&](auto fastc) {
+    for (int tile = 0; tile < ntiles; tile += 2) {
+      do_tile(tile, std::integral_constant<int, 0>{}, fastc);
+      if (tile + 1 < ntiles) do_tile(tile + 1, std::integral_constant<int, 1>{}, fastc);
+    }
+  };
+  // First with the softmax reference fixed at zero -- no maximum, no rescaling, nothing between the scores and
+  // their exponentials: p = exp2(cs * s), exact as long as neither a probability nor a row sum leaves the range of
+  // fp32 (any reference gives the same O / l).  Whether it did is known from the row sums at the end: a sum that is
+  // infinite, not a number, or outside 2^-80 .. 2^80 sends the whole workgroup through its band again with the
+  // running maximum of Eq. 1's usual online form (scores beyond +-55 / scale: not what attention logits look like).
+  m_ref = 0.f;
+  run_band(std::true_type{});
+  float l_tot = sum_with_other_half(l_run);
+  const bool out_of_range = s < n && !(l_tot > 0x1p-80f && l_tot < 0x1p80f);
+  if (__syncthreads_or(out_of_range ? 1 : 0)) {
+    m_ref = -INFINITY;
+    l_run = 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    init_ring();
+    __syncthreads();  // ring visible
+    load_tile(0, 0);
+    run_band(std::false_type{});
+    l_tot = sum_with_other_half(l_run);
   }
 
   // ---- epilogue: normalise, transpose through LDS, scatter rows to their original positions
-  const float l_tot = sum_with_other_half(l_run);
   const float inv_l = 1.f / l_tot;
   const size_t head_row0 = ((size_t)b * p.Hq + hq) * n;
   const size_t my_row = head_row0 + orig_q;  // this lane's output row (valid when s < n)

@@ -100,7 +100,9 @@ def test_decode_continues_the_prompt_pass():
         sa.sa_decode_fwd(full, Q[:, :, length - 1].contiguous(), K, V, length, Y, L, ws)
         torch.cuda.synchronize()
         assert (Y.float() - Yp[:, :, length - 1].float()).abs().max().item() <= 2e-2
-        assert (L - Lp[:, :, length - 1]).abs().max().item() <= 1e-3
+        # the prefill's row sum is taken from the bf16-rounded probabilities that build its output (|dLSE| <= 2^-9
+        # plus the exp/log error), the decoding step sums in fp32: the two agree to the bf16 LSE bar
+        assert (L - Lp[:, :, length - 1]).abs().max().item() <= 4e-3
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,n,d,lens", [

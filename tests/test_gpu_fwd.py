@@ -120,6 +120,45 @@ def test_bf16_later_keys_dominate():
     run_fwd(1, 2, 1, 900, 128, 128, CIRC, 1, "bf16", perm_H=2, seed=51, k_growth=25.0)
 
 
+@pytest.mark.parametrize("shift", [150.0, -150.0, 0.0, 30.0, -30.0])
+@pytest.mark.parametrize("d,causal", [(128, 1), (64, 1), (64, 0)])
+def test_bf16_scores_far_from_zero(shift, d, causal):
+    """The kernel first runs a band with the softmax reference fixed at zero and goes through it again with the
+    running maximum when a row sum leaves the range of that form.  Scores around +150 (every exponential
+    overflows), around -150 (every exponential underflows) and rows of both kinds side by side in one workgroup
+    (shift 0 here: the sign alternates with the original position) must all come out as the oracle's
+    max-subtracted softmax does; so must scores around +-30, which the zero-reference form still holds (row sums
+    near 2^43 and 2^-43)."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    B, Hq, Hkv, n, w = 1, 4, 2, 700, 128
+    wl, x = U.make_case(B, Hq, Hkv, n, d, w, "bf16", 1, 1, seed=90 + d)
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    target = 150.0 if shift == 0.0 else abs(shift)
+    amp = np.sqrt(target * np.sqrt(d))         # (amp u) . (amp u) / sqrt(d) = target
+    sign = np.where(np.arange(n) % 2 == 0, 1.0, -1.0) if shift == 0.0 else np.full(n, np.sign(shift))
+    x["Q"] = synth.round_to_bf16((x["Q"] + (sign[:, None] * amp * u)[None, None]).astype(np.float32))
+    x["K"] = synth.round_to_bf16((x["K"] + (amp * u)[None, None, None]).astype(np.float32))
+    print(f"case fwd far-from-zero shift{shift} d{d} causal{causal}", flush=True)
+    Yr, Lr = orc.sa_fwd(U.orc_desc(wl, CIRC, causal), x["Q"], x["K"], x["V"], x["perm"])
+    if target == 150.0:
+        assert np.abs(Lr).min() > 60.0         # the rows really are out of the zero-reference form's range
+    else:
+        assert 12.0 < np.abs(Lr).min() and np.abs(Lr).max() < 52.0   # and these inside it (ln 2^80 = 55.5)
+    Q, K, V = (U.to_dev(x[k], "bf16") for k in "QKV")
+    perm = torch.from_numpy(x["perm"]).to(U.DEV)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd(U.sa_desc(wl, CIRC, causal), Q, K, V, perm, Y, L)
+    torch.cuda.synchronize()
+    U.assert_close(U.to_np64(Y), Yr, "bf16", "Y")
+    # LSE is of order 150 here: its fp32 representation alone has steps of 1.5e-5, the bf16 bar applies on top
+    assert np.abs(U.to_np64(L) - Lr).max() <= 4e-3 + 1e-4
+
+
 def test_bf16_long_sequence_uses_32bit_indices():
     """n > 65535: original positions no longer fit the 16-bit mask path."""
     run_fwd(1, 1, 1, 66000, 64, 64, CIRC, 1, "bf16", seed=52)
