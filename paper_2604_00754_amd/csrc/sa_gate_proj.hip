@@ -12,7 +12,9 @@
 // the tiles are staged row-major (+16 B row padding) and read with plain 16-byte loads.  The product
 // is formed transposed (A operand = weight rows, B operand = token rows): a lane then owns one
 // token and each accumulator quad four consecutive output features, i.e. 8 contiguous bytes of
-// Y_x and Y.
+// Y_x and Y.  The forward walks the contraction in rotated order, ending with the 128 input features
+// that are the workgroup's own output features: the y_x values the epilogue multiplies the gates with
+// are then the token tiles still lying in the two LDS buffers, and are not loaded a second time.
 //
 // Backward (given dY; g_x saved by the forward):
 //   dz_x = dY * y_x * g_x * (1 - g_x)                     element-wise pass, rounded to bf16
@@ -71,7 +73,12 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
   // loader: 128 rows x 8 chunks of 16 bytes per operand tile, 4 chunks per thread and operand
   const int lrow = tid >> 3, lchunk = tid & 7;  // rows lrow + 32*j
   u32x4 areg[4], wreg[4];
-  auto load_tiles = [&](const bf16_t* Yx, const bf16_t* Wx, int kk) {
+  // Forward: the contraction steps are taken in rotated order, ending with the two that cover the workgroup's own
+  // 128 output features, so that the token tiles left in the two buffers are the Y_x values Eq. 5 needs at the
+  // output positions (the epilogue reads them from LDS instead of from memory).
+  const int krot = MODE == GP_FORWARD ? (o0 / TK + 2) % nk : 0;  // (dm is a multiple of TN = 2 TK: nk >= 2)
+  auto load_tiles = [&](const bf16_t* Yx, const bf16_t* Wx, int step) {
+    const int kk = step + krot < nk ? step + krot : step + krot - nk;
     const int k0 = kk * TK, h = k0 / D, e0 = k0 % D;
     const bf16_t* abase = Yx + ((size_t)b * H + h) * n * (size_t)D + e0 + lchunk * 8;
     const bf16_t* wbase = Wx + (size_t)k0 + lchunk * 8;
@@ -105,10 +112,11 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
 
   // Output rows leave through a wave-private LDS area: the accumulator layout gives a lane 8-byte pieces of
   // 32 different rows, the staged copy lets 8 lanes write one full 128-byte piece of a row (non-temporal:
-  // the outputs are written once).  stage_out is called after a workgroup barrier (the area overlays the
-  // GEMM buffers).
+  // the outputs are written once).  Staging follows a workgroup barrier: the area lies on the two weight
+  // tiles (waves 0, 1 on the first buffer's, waves 2, 3 on the second's), so the token tiles stay readable.
   constexpr int OSTR = 64 + 8;  // bf16 per staged row (64 features of one token + 16 B pad)
-  bf16_t* ostage = reinterpret_cast<bf16_t*>(smem) + wave * 64 * OSTR;
+  static_assert(2 * 64 * OSTR * 2 == TILE_BYTES, "two waves' staging rows fill one weight tile");
+  bf16_t* ostage = reinterpret_cast<bf16_t*>(smem + (wave >> 1) * GBUF_BYTES + TILE_BYTES) + (wave & 1) * 64 * OSTR;
   auto stage_put = [&](int fi, int ti, int q, u32x2 w) {
     *reinterpret_cast<u32x2*>(ostage + (32 * ti + c32) * OSTR + 32 * fi + 8 * q + 4 * g2) = w;
   };
@@ -172,6 +180,9 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
     bf16_t* Gx = reinterpret_cast<bf16_t*>(p.G_x[x]);
     const bf16_t* E1 = reinterpret_cast<const bf16_t*>(p.E1);
     const bf16_t* E2 = reinterpret_cast<const bf16_t*>(p.E2);
+    // step nk-2 left features o0 .. o0+63 of the token tile in its buffer, step nk-1 the next 64: this wave's 64
+    // features are in the buffer of step nk-2+wn (the output staging area below lies on the weight tiles only)
+    const bf16_t* Ay = reinterpret_cast<const bf16_t*>(smem + ((nk - 2 + wn) & 1) * GBUF_BYTES) + (64 * wm + c32) * GSTR + 4 * g2;
     if (MODE == GP_FORWARD && Gx) __syncthreads();  // every wave has read its last operands: the area is free
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
@@ -185,7 +196,7 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
           const int o = o0 + 64 * wn + 32 * fi + 8 * q + 4 * g2;  // first of four consecutive features
           const size_t at = (((size_t)b * H + o / D) * n + tk) * D + o % D;
           if (MODE == GP_FORWARD) {
-            const u32x2 y = *reinterpret_cast<const u32x2*>(Yx + at);
+            const u32x2 y = *reinterpret_cast<const u32x2*>(Ay + 32 * ti * GSTR + 32 * fi + 8 * q);
             const float yv[4] = {bf16lo(y[0]), bf16hi(y[0]), bf16lo(y[1]), bf16hi(y[1])};
             float gv[4];
 #pragma unroll
