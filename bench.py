@@ -246,7 +246,7 @@ def backward_setup(sa, synth, dev, name):
 
 
 def backward_roofline(sa, synth, dev, steps, warmup):
-    """The second half of the metric: sa_bwd (row-sum pass, dQ kernel, dK/dV kernel) on the pre-training
+    """The second half of the metric: sa_bwd (dQ kernel, which also forms the row sums D, then dK/dV kernel) on the pre-training
     shape B=4, H=16, n=8192, d=64, w=256, against both roofs.  Algorithmic flop: 5 contractions over the window
     band, 10 n W d per (b, h); algorithmic bytes: Q, K, V, Y, dY, LSE and the index tensor in, dQ, dK, dV out."""
     wl, call, keep = backward_setup(sa, synth, dev, "pretrain_fwdbwd_8k")
@@ -259,14 +259,14 @@ def backward_roofline(sa, synth, dev, steps, warmup):
     tflops, gbs = flop / (mean_ms * 1e-3) / 1e12, nbytes / (mean_ms * 1e-3) / 1e9
     traffic, source = measured_traffic("sa_bwd", "pretrain_fwdbwd_8k")
     return {"op": "sa_bwd", "workload": "pretrain_fwdbwd_8k", "shape": "B4 H16 n8192 d64 w256 bf16",
-            "kernels": ["bwd_prepare_kernel", "bwd_dq_mfma_bf16_kernel<64, 2>", "bwd_dkv_mfma_bf16_kernel<64, 2>"],
+            "kernels": ["bwd_dq_mfma_bf16_kernel<64, 2>", "bwd_dkv_mfma_bf16_kernel<64, 2>"],
             "dominant_kernel": "bwd_dkv_mfma_bf16_kernel<64, 2>",
             "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
             "algorithmic_bytes": nbytes, "traffic": traffic, "traffic_source": source,
             "mfma": {"achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS,
                      "algorithmic_flop": flop},
             "avg_call_ms": mean_ms, "median_call_ms": float(np.median(samples)), "min_call_ms": float(np.min(samples)),
-            "note": "one sa_bwd call = three kernels; the nearer roof at this shape is HBM (frac), the MFMA figure beside it"}
+            "note": "one sa_bwd call = two kernels; the nearer roof at this shape is HBM (frac), the MFMA figure beside it"}
 
 
 def table3_sweep(sa, synth, dev):

@@ -452,17 +452,9 @@ sa_status sa_dual_path_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void
   float* D[2] = {reinterpret_cast<float*>(base + w.off_Db), reinterpret_cast<float*>(base + w.off_Da)};
   const sa_desc* dsc[2] = {swa_d, sa_d};
   for (int x = 0; x < 2; ++x) {
-    sa::Prep pr = {};
-    pr.rows = sa_d->B * sa_d->Hq * sa_d->n;
-    pr.d = sa_d->d;
-    pr.bf16 = 1;
-    pr.dY = dO[x];
-    pr.Y_a = Yx[x];
-    pr.D_a = D[x];
-    e = sa::launch_bwd_prepare(pr, st);
-    if (e != hipSuccess) return hip_status(e);
     Pass p = make_pass(dsc[x], Q, K, V, x == 0 ? nullptr : perm);
-    p.dO = dO[x]; p.lse_in = lse[x]; p.Dsum = D[x];
+    p.dO = dO[x]; p.lse_in = lse[x];
+    p.O_rows = Yx[x]; p.Dsum_out = D[x];  // the dQ kernel forms rowsum(dO o O) from the rows it holds
     p.dQ = dQ; p.dK = dK; p.dV = dV; p.accumulate = x;
     e = run_bwd(dsc[x], p, st);
     if (e != hipSuccess) return hip_status(e);
@@ -562,7 +554,9 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   pr.lse_a = LSE_sa; pr.lse_b = LSE_swa;
   pr.L_a = fold ? reinterpret_cast<float*>(base + w.off_dOa) : nullptr;
   pr.L_b = fold ? pr.L_a + (size_t)pr.rows : nullptr;
-  hipError_t e = sa::launch_bwd_prepare(pr, st);
+  // ungated bf16: no separate pass, the dQ kernel forms rowsum(dY o Y) from the rows it holds
+  const bool rowsum_in_dq = !gated && sa_d->dtype == SA_BF16;
+  hipError_t e = rowsum_in_dq ? hipSuccess : sa::launch_bwd_prepare(pr, st);
   if (e != hipSuccess) return hip_status(e);
 
   if (gated) {
@@ -578,6 +572,7 @@ sa_status sa_bwd(const sa_desc* sa_d, const sa_desc* swa_d, const void* Q, const
   b.dO = gated && !fold ? pr.dO_a : dY;
   b.lse_in = fold ? pr.L_a : LSE_sa;
   b.Dsum = pr.D_a;
+  if (rowsum_in_dq) { b.O_rows = Y_sa; b.Dsum_out = pr.D_a; }
   b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = gated ? 1 : 0;
   return hip_status(run_bwd(sa_d, b, st));
 }
@@ -599,16 +594,6 @@ sa_status sa_bwd_rope(const sa_desc* c, const void* Q, const void* K, const void
   hipStream_t st = (hipStream_t)stream;
   char* base = reinterpret_cast<char*>(ws);
 
-  sa::Prep pr = {};
-  pr.rows = c->B * c->Hq * c->n;
-  pr.d = c->d;
-  pr.bf16 = 1;
-  pr.dY = dY;
-  pr.Y_a = Y;
-  pr.D_a = reinterpret_cast<float*>(base + w.off_Da);
-  hipError_t e = sa::launch_bwd_prepare(pr, st);
-  if (e != hipSuccess) return hip_status(e);
-
   Pass b = make_pass(c, Q, K, V, perm);
   b.rope_table = rope_table;
   b.rope_interleaved = interleaved;
@@ -616,7 +601,8 @@ sa_status sa_bwd_rope(const sa_desc* c, const void* Q, const void* K, const void
   b.Q_rot = base + w.total;
   b.dO = dY;
   b.lse_in = LSE;
-  b.Dsum = pr.D_a;
+  b.O_rows = Y;  // the dQ kernel forms rowsum(dY o Y) from the rows it holds
+  b.Dsum_out = reinterpret_cast<float*>(base + w.off_Da);
   b.dQ = dQ; b.dK = dK; b.dV = dV; b.accumulate = 0;
   return hip_status(sa::launch_bwd_mfma_bf16(b, st));
 }

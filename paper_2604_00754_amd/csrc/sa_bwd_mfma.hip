@@ -8,7 +8,9 @@
 // Two kernels, both recomputing S from Q and K:
 //   dQ kernel    -- a workgroup owns 128 query slots (as in the forward) and walks key tiles;
 //                   S^T and dP^T are produced in the "lane = query" layout, dS^T feeds
-//                   dQ^T += K^T dS^T with K read from LDS by the transposing load.
+//                   dQ^T += K^T dS^T with K read from LDS by the transposing load.  Given the forward's
+//                   output rows it also forms D for its queries (it holds their dO rows anyway) and
+//                   leaves D for the other kernel, so the ungated call has no separate row-sum pass.
 //   dK/dV kernel -- a workgroup owns 128 key slots and walks query tiles (and the query heads of
 //                   its group); S and dP are produced in the "lane = key" layout, P and dS feed
 //                   dV^T += dO^T P and dK^T += Q^T dS with dO and Q read by the transposing load.
@@ -226,10 +228,12 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_d
   const int orig_q = slot_to_orig(perm, min(s, n - 1));
   load_idx(0);
   bf16x8 qf[D / 16], gf[D / 16];
+  float Dq = 0.f;
   {
-    u32x4 qrow[C::SP], grow[C::SP];
+    u32x4 qrow[C::SP], grow[C::SP], orow[C::SP];
     stationary_rows<C, D>(Qh, st_src, lane, qrow);
     stationary_rows<C, D>(dOh, st_src, lane, grow);
+    if (p.O_rows) stationary_rows<C, D>(reinterpret_cast<const bf16_t*>(p.O_rows) + head_row0 * D, st_src, lane, orow);
     request_tile(0);
     if (ntiles > 1) load_idx(1);
     bf16_t* stage = reinterpret_cast<bf16_t*>(smem + C::BUF_BYTES) + wave * 32 * C::STR;  // buffer 1 is still free
@@ -240,6 +244,23 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_d
     stationary_put<C>(stage, lane, grow);
     wave_lds_sync();
     stationary_get<C, D>(stage, lane, gf);
+    if (p.O_rows) {
+      // D = rowsum(dO o O) of the lane's query row, from the rows this wave holds anyway: the output rows take the
+      // same way as Q and dO, each lane sums its half of the row and the two halves are added
+      bf16x8 of[D / 16];
+      wave_lds_sync();
+      stationary_put<C>(stage, lane, orow);
+      wave_lds_sync();
+      stationary_get<C, D>(stage, lane, of);
+      float part = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        const u32x4 gw = __builtin_bit_cast(u32x4, gf[kk]), ow = __builtin_bit_cast(u32x4, of[kk]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) part = fmaf(bf16hi(gw[e]), bf16hi(ow[e]), fmaf(bf16lo(gw[e]), bf16lo(ow[e]), part));
+      }
+      Dq = sum_with_other_half(part);
+    }
   }
   const float2* rope_row = p.rope_table ? reinterpret_cast<const float2*>(p.rope_table) + (size_t)orig_q * (D / 2) : nullptr;
   if (rope_row) {
@@ -253,7 +274,11 @@ __global__ __launch_bounds__(NT, D == 128 ? DQ128_WAVES : DQ64_WAVES) void bwd_d
     }
   }
   const float lse2 = p.lse_in[head_row0 + orig_q] * kLog2e;
-  const float Dq = p.Dsum[head_row0 + orig_q];
+  if (p.O_rows) {
+    if (g2 == 0 && s < n) p.Dsum_out[head_row0 + orig_q] = Dq;
+  } else {
+    Dq = p.Dsum[head_row0 + orig_q];
+  }
 
   int koff[D / 16], troff[D / 32][2];
   swizzled_row_offsets<D>(lane, koff);
@@ -775,7 +800,8 @@ hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (p.n < 1 || p.B < 1 || p.Hq < 1 || p.Hkv < 1 || p.g * p.Hkv != p.Hq) return hipErrorInvalidValue;
   if (p.win.L < 0 || p.win.R < 0 || p.win.L >= p.n || p.win.R >= p.n) return hipErrorInvalidValue;
   if (p.win.circular && p.win.L + p.win.R + 1 > p.n) return hipErrorInvalidValue;
-  if (!p.dO || !p.lse_in || !p.Dsum || !p.dQ || !p.dK || !p.dV) return hipErrorInvalidValue;
+  if (!p.dO || !p.lse_in || !p.dQ || !p.dK || !p.dV) return hipErrorInvalidValue;
+  if (p.O_rows ? !p.Dsum_out : !p.Dsum) return hipErrorInvalidValue;
   if (!(p.d == 64 || p.d == 128)) return hipErrorNotSupported;
   if ((long)p.n * p.d * 2 >= (1L << 31)) return hipErrorNotSupported;  // 32-bit row offsets inside a head
   if (p.rope_dk && !p.rope_table) return hipErrorInvalidValue;
@@ -784,6 +810,7 @@ hipError_t launch_bwd_mfma_bf16(const Pass& p, hipStream_t st) {
   if (e != hipSuccess) return e;
   Pass kv = p;
   if (p.rope_table) kv.Q = p.Q_rot;  // the dQ kernel has left the rotated rows there
+  if (p.O_rows) kv.Dsum = p.Dsum_out;  // and the row sums here
   if (p.perm && p.perm_H != 1 && p.g > 1) {
     // every query head of a group has its own slot order: one pass per head, summed in place
     Pass q = kv;

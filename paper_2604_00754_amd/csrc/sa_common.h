@@ -48,6 +48,8 @@ struct Pass {
   const void* dO;       // gradient w.r.t. this branch's output [B,Hq,n,d]
   const float* lse_in;  // [B,Hq,n]
   const float* Dsum;    // rowsum(dO * O) [B,Hq,n]
+  const void* O_rows;   // bf16 path, optional: this branch's output rows [B,Hq,n,d]; when given, the dQ kernel forms
+  float* Dsum_out;      // rowsum(dO * O) itself from its stationary rows and leaves it here for the dK/dV kernel
   void* dQ;
   void* dK;
   void* dV;
