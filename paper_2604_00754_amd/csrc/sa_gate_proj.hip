@@ -201,7 +201,7 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
             float gv[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              gv[e] = sigmoidf_exact(acc[fi][ti][4 * q + e]);
+              gv[e] = sigmoidf_rcp(acc[fi][ti][4 * q + e]);
               out[fi][ti][4 * q + e] = fmaf(gv[e], yv[e], out[fi][ti][4 * q + e]);
             }
             if (Gx) {
