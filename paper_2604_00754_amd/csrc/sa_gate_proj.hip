@@ -136,6 +136,27 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
     wave_lds_sync();
   };
 
+  // The other way round: the wave's 64 tokens x 64 features of a tensor come in as whole 128-byte pieces of rows
+  // and are handed out in the accumulator layout (rows past n: the last row's values, never stored).
+  auto stage_fetch_rows = [&](const bf16_t* src, u32x4* v) {
+    const int o = o0 + 64 * wn;
+    const size_t col = (size_t)(o % D) + (lane & 7) * 8;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int token = min(i0 + 64 * wm + pass * 8 + (lane >> 3), n - 1);
+      v[pass] = *reinterpret_cast<const u32x4*>(src + (((size_t)b * H + o / D) * n + token) * D + col);
+    }
+  };
+  auto stage_fetch_put = [&](const u32x4* v) {
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass)
+      *reinterpret_cast<u32x4*>(ostage + (pass * 8 + (lane >> 3)) * OSTR + (lane & 7) * 8) = v[pass];
+    wave_lds_sync();
+  };
+  auto stage_get = [&](int fi, int ti, int q) -> u32x2 {
+    return *reinterpret_cast<const u32x2*>(ostage + (32 * ti + c32) * OSTR + 32 * fi + 8 * q + 4 * g2);
+  };
+
   const int branches = p.Y_x[1] ? 2 : 1;
   for (int x = 0; x < branches; ++x) {
     const bf16_t* Yx = reinterpret_cast<const bf16_t*>(p.Y_x[x]);
@@ -184,6 +205,24 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
     // features are in the buffer of step nk-2+wn (the output staging area below lies on the weight tiles only)
     const bf16_t* Ay = reinterpret_cast<const bf16_t*>(smem + ((nk - 2 + wn) & 1) * GBUF_BYTES) + (64 * wm + c32) * GSTR + 4 * g2;
     if (MODE == GP_FORWARD && Gx) __syncthreads();  // every wave has read its last operands: the area is free
+    u32x2 e1[2][2][4];
+    if (MODE == GP_BWD_INPUT) {
+      // dY and g_x at the output positions: whole rows through the staging area (the accumulator layout would
+      // ask memory for 8-byte pieces of 32 rows per instruction)
+      u32x4 r1[8], r2[8];
+      stage_fetch_rows(E1, r1);
+      stage_fetch_rows(E2, r2);
+      __syncthreads();  // every wave has read its last operands: the area is free
+      stage_fetch_put(r1);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) e1[ti][fi][q] = stage_get(fi, ti, q);
+      wave_lds_sync();
+      stage_fetch_put(r2);
+    }
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       const int token = i0 + 64 * wm + 32 * ti + c32;
@@ -211,7 +250,7 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
               stage_put(fi, ti, q, w);
             }
           } else {
-            const u32x2 a = *reinterpret_cast<const u32x2*>(E1 + at), c = *reinterpret_cast<const u32x2*>(E2 + at);
+            const u32x2 a = e1[ti][fi][q], c = stage_get(fi, ti, q);
             out[fi][ti][4 * q + 0] = fmaf(bf16lo(a[0]), bf16lo(c[0]), acc[fi][ti][4 * q + 0]);
             out[fi][ti][4 * q + 1] = fmaf(bf16hi(a[0]), bf16hi(c[0]), acc[fi][ti][4 * q + 1]);
             out[fi][ti][4 * q + 2] = fmaf(bf16lo(a[1]), bf16lo(c[1]), acc[fi][ti][4 * q + 2]);
