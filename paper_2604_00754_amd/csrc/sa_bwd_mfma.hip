@@ -101,7 +101,7 @@ __device__ __forceinline__ void stationary_get(const bf16_t* stage, int lane, bf
 
 // Write a wave's transposed accumulators (lane = row c32 of the output, 4 consecutive values along
 // d per accumulator quad) as 32 bf16 rows to their original positions: src[pass] for the rows this
-// lane moves (as stationary_src gave them), orig_mine for the lane's own row c32.  `accumulate`
+// lane moves (as stationary_src gave them).  `accumulate`
 // first adds what the rows already hold (the other branch's gradient, stored as bf16) in fp32 and rounds
 // the sum: two roundings in all, one per branch.  The staging area is private to the wave.
 // trow != nullptr: the rows are first turned back by the angle of their position (the transpose of RoPE).
@@ -111,7 +111,18 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
                                            const float2* trow = nullptr, int interleaved = 0) {
   const int g2 = lane >> 5, c32 = lane & 31;
   if (trow) rope_transpose_accumulators<D>(acc, trow, g2, interleaved);
-  const bf16_t* mine = out_head + (size_t)orig_mine * D;
+  if (accumulate) {
+    // what the rows hold comes in as whole rows, the way they leave (in the accumulator layout a lane would ask
+    // memory for 8-byte pieces of 32 rows per instruction), and waits in the staging area for the sums
+    u32x4 old[C::SP];
+#pragma unroll
+    for (int pass = 0; pass < C::SP; ++pass)
+      old[pass] = *reinterpret_cast<const u32x4*>(out_head + (size_t)src[pass] * D + (lane % C::VPR) * 8);
+#pragma unroll
+    for (int pass = 0; pass < C::SP; ++pass)
+      *reinterpret_cast<u32x4*>(stage + (pass * C::WRPP + lane / C::VPR) * C::STR + (lane % C::VPR) * 8) = old[pass];
+    wave_lds_sync();
+  }
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -119,7 +130,7 @@ __device__ __forceinline__ void store_rows(f32x16* acc, float mul, bf16_t* stage
       float v0 = acc[db][4 * mq + 0] * mul, v1 = acc[db][4 * mq + 1] * mul;
       float v2 = acc[db][4 * mq + 2] * mul, v3 = acc[db][4 * mq + 3] * mul;
       if (accumulate) {
-        const u32x2 o = *reinterpret_cast<const u32x2*>(mine + 32 * db + 8 * mq + 4 * g2);
+        const u32x2 o = *reinterpret_cast<const u32x2*>(stage + c32 * C::STR + 32 * db + 8 * mq + 4 * g2);
         v0 += bf16lo(o[0]); v1 += bf16hi(o[0]);
         v2 += bf16lo(o[1]); v3 += bf16hi(o[1]);
       }

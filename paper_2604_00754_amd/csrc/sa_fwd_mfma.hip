@@ -504,12 +504,29 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
       ga = sigmoidf_exact(load_gate(p.gate_this, r, p.gate_f32));
       gb = sigmoidf_exact(load_gate(p.gate_other, r, p.gate_f32));
     }
+    // the other branch's rows come in as whole rows through the staging area, the way this branch's leave (in the
+    // accumulator layout a lane would ask memory for 8-byte pieces of 32 rows per instruction)
+    {
+      int src_row[NP];
+#pragma unroll
+      for (int pass = 0; pass < NP; ++pass) src_row[pass] = rowstash[wave * 32 + pass * C::WRPP + lane / C::CPR];
+      u32x4 orow[NP];
+#pragma unroll
+      for (int pass = 0; pass < NP; ++pass)
+        orow[pass] = load_row_chunk<D>(reinterpret_cast<const bf16_t*>(p.Y_other) + head_row0 * D, src_row[pass], chunk16);
+      if (!p.Y) __syncthreads();  // nothing has claimed the staging area from the tile buffers yet
+      wave_lds_sync();            // (otherwise: the stores of this branch's rows have read the area)
+#pragma unroll
+      for (int pass = 0; pass < NP; ++pass)
+        *reinterpret_cast<u32x4*>(Os + (pass * C::WRPP + lane / C::CPR) * C::QSTR + chunk16 * 8) = orow[pass];
+      wave_lds_sync();
+    }
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
       for (int mq = 0; mq < 4; ++mq) {
         const size_t e0 = r * D + 32 * db + 8 * mq + 4 * g2;
-        const u32x2 ob = *reinterpret_cast<const u32x2*>(reinterpret_cast<const bf16_t*>(p.Y_other) + e0);
+        const u32x2 ob = *reinterpret_cast<const u32x2*>(Os + c32 * C::QSTR + 32 * db + 8 * mq + 4 * g2);
         const float o[4] = {bf16lo(ob[0]), bf16hi(ob[0]), bf16lo(ob[1]), bf16hi(ob[1])};
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
