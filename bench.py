@@ -85,6 +85,26 @@ def time_side(fn, steps, warmup):
     return wall, float(np.median(time_op.last_samples_ms))
 
 
+def time_pair(fn_a, fn_b, steps, warmup):
+    """Two variants of one call, timed alternately (a, b, a, b, ...) so that a drift of the clocks during the
+    measurement falls on both alike; the median per-call HIP-event time of each."""
+    for _ in range(warmup):
+        fn_a()
+        fn_b()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for a0, a1, b0, b1 in ev:
+        a0.record()
+        fn_a()
+        a1.record()
+        b0.record()
+        fn_b()
+        b1.record()
+    torch.cuda.synchronize()
+    return (float(np.median([e[0].elapsed_time(e[1]) for e in ev])),
+            float(np.median([e[2].elapsed_time(e[3]) for e in ev])))
+
+
 def executed_flop(n, w, d, B, Hq, BM=128, BN=64):
     """Flop of the matrix instructions the forward kernel issues at this shape (symmetric circular
     window): per wave (32 query slots) every 32-key block of the workgroup's tiles that any of its
@@ -171,9 +191,10 @@ def training_ops(sa, synth, dev, reps):
     Gsa, Gswa, dYsa, dYswa = (torch.empty_like(Q) for _ in range(4))
     dWsa, dWswa = torch.empty_like(Wsa), torch.empty_like(Wswa)
     wsg = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATE_PROJ_BWD), device=dev, dtype=torch.uint8)
-    _, t_gp = time_side(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa), reps, 2)
-    # inference form: the gate values are not kept (two of the three output tensors are not written)
-    _, t_gpi = time_side(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, None, None), reps, 2)
+    # training form and inference form (the gate values are not kept: two of the three output tensors are not
+    # written), timed alternately
+    t_gp, t_gpi = time_pair(lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa),
+                            lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, None, None), reps, 2)
     _, t_gpb = time_side(lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa,
                                                    dWsa, dWswa, wsg), reps, 2)
     # the whole layer of Alg. 2 in one call each way (both branches + gate projections)
@@ -416,6 +437,10 @@ def main():
     bwd_block = None
     other = {}
     if not args.only_step:
+        # clocks ramp over the first tens of milliseconds of load: bring them up before the first side measurement
+        for _ in range(100):
+            sa.sa_fwd(desc, Q, K, V, perm, Y, LSE)
+        torch.cuda.synchronize()
         # the same call with the identity permutation and the one-sided causal window (plain SWA)
         swa_desc = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_ONE_SIDED, 1, sa.SA_BF16,
                                 0.0, 1, 1)
