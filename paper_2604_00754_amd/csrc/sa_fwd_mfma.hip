@@ -451,6 +451,7 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
     load_tile(0, 0);
     run_band(std::false_type{});
     l_tot = sum_with_other_half(l_run);
+    __syncthreads();  // every wave is through its last tile (on the other path the vote above says so)
   }
 
   // ---- epilogue: normalise, transpose through LDS, scatter rows to their original positions
@@ -465,8 +466,10 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 
   // accumulator (db, 4mq..4mq+3) of a lane = elements 32db + 8mq + 4g2 .. +3 of its row
   bf16_t* Os = reinterpret_cast<bf16_t*>(smem) + wave * 32 * C::QSTR;
+  bool area_free = true;  // the barrier that ended the tile loop has freed the staging area for its first use
   auto stage_and_store = [&](const f32x16* acc, void* dst_tensor) {
-    __syncthreads();  // the staging area is free (last tile consumed / previous staging pass stored)
+    if (!area_free) __syncthreads();  // the previous staging pass is stored
+    area_free = false;
     int le = lane;  // the lane's staging address is formed here, from a copy the optimiser cannot trace back to
     asm volatile("" : "+v"(le));  // the prologue's (equal) one, which it would otherwise keep across the tile loop
     bf16_t* mine = Os + (le & 31) * C::QSTR + 4 * (le >> 5);
@@ -514,8 +517,8 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass)
         orow[pass] = load_row_chunk<D>(reinterpret_cast<const bf16_t*>(p.Y_other) + head_row0 * D, src_row[pass], chunk16);
-      if (!p.Y) __syncthreads();  // nothing has claimed the staging area from the tile buffers yet
-      wave_lds_sync();            // (otherwise: the stores of this branch's rows have read the area)
+      area_free = false;
+      wave_lds_sync();  // the stores of this branch's rows, if there were any, have read the area
 #pragma unroll
       for (int pass = 0; pass < NP; ++pass)
         *reinterpret_cast<u32x4*>(Os + (pass * C::WRPP + lane / C::CPR) * C::QSTR + chunk16 * 8) = orow[pass];
