@@ -211,7 +211,8 @@ __global__ __launch_bounds__(NT, D == 64 ? (GATED ? 3 : FWD_WGS64) : (GATED ? 2 
     for (int pass = 0; pass < NP; ++pass)
       *reinterpret_cast<u32x4*>(Qs + (pass * C::WRPP + lane / C::CPR) * C::QSTR + chunk16 * 8) = v[pass];
   }
-  __syncthreads();  // Q rows staged (tile 0 is waited for at the top of the tile loop)
+  wave_lds_sync();  // Q rows staged: the rows are this wave's own (tile 0 is waited for at the top of the tile loop,
+                    // whose barrier also tells everyone that the staging area may take tile 1)
   bf16x8 qf[D / 16];
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk)
