@@ -37,7 +37,9 @@ def run_bwd(B, Hq, Hkv, n, d, w, window, causal, dtype, perm_B=1, perm_H=1, seed
     L = torch.empty((B, Hq, n), device=U.DEV, dtype=torch.float32)
     sa.sa_fwd(desc, Q, K, V, perm, Y, L)
     dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
-    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=U.DEV, dtype=torch.uint8)
+    # the workspace enters as NaN bit patterns: whatever a kernel reads from it (the row sums the dQ kernel leaves for
+    # the dK/dV kernel) must have been written by the same call
+    ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD),), 255, device=U.DEV, dtype=torch.uint8)
     sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
     torch.cuda.synchronize()
     grad_close(U.to_np64(dQ), dQr, dtype, "dQ")
@@ -73,7 +75,7 @@ def run_gated_bwd(B, Hq, Hkv, n, d, w, dtype, perm_B=1, perm_H=1, per_dim=0, gat
     sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, tga, tgl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
     dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
     dga, dgl = torch.full_like(tga, float("nan")), torch.full_like(tgl, float("nan"))
-    ws = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD), device=U.DEV, dtype=torch.uint8)
+    ws = torch.full((sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD),), 255, device=U.DEV, dtype=torch.uint8)
     sa.sa_bwd(dsa, dswa, Q, K, V, perm, tga, tgl, Ysa, Yswa, Lsa, Lswa, dY, dQ, dK, dV, dga, dgl, ws)
     torch.cuda.synchronize()
     for got, r, what in ((dQ, ref[0], "dQ"), (dK, ref[1], "dK"), (dV, ref[2], "dV")):

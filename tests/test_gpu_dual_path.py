@@ -47,7 +47,7 @@ def run_layer(B, Hq, Hkv, n, d, w, perm_H=1, seed=0, backward=True, train=True):
     rb = orc.dual_path_bwd(osa, oswa, x["Q"], x["K"], x["V"], x["perm"], Wsa, Wswa, x["dY"])
     dY = dev(x["dY"])
     dQ, dK, dV, dWa, dWb = nan(Q), nan(K), nan(V), nan(tWa), nan(tWb)
-    ws = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_DUAL_PATH_BWD), device=U.DEV, dtype=torch.uint8)
+    ws = torch.full((sa.sa_workspace_bytes(dsa, sa.SA_OP_DUAL_PATH_BWD),), 255, device=U.DEV, dtype=torch.uint8)
     sa.sa_dual_path_bwd(dsa, dswa, Q, K, V, perm, tWa, tWb, Ya, Yb, Ga, Gb, La, Lb, dY, dQ, dK, dV, dWa, dWb, ws)
     torch.cuda.synchronize()
     for name, got in (("dQ", dQ), ("dK", dK), ("dV", dV), ("dWsa", dWa), ("dWswa", dWb)):

@@ -102,7 +102,7 @@ def run_bwd_case(B, H, n, d, seed, dual=True):
     dYsa, dWsa = nan(tYsa), nan(tWsa)
     dYswa, dWswa = (nan(tYsa), nan(tWsa)) if dual else (None, None)
     op = sa.SA_OP_GATE_PROJ_BWD if dual else sa.SA_OP_GATE_PROJ_BWD_SINGLE
-    ws = torch.empty(sa.sa_workspace_bytes(desc, op), device=U.DEV, dtype=torch.uint8)
+    ws = torch.full((sa.sa_workspace_bytes(desc, op),), 255, device=U.DEV, dtype=torch.uint8)
     sa.sa_gate_proj_bwd(desc, tYsa, tYswa, tWsa, tWswa, Ga, Gb, tdY, dYsa, dYswa, dWsa, dWswa, ws)
     torch.cuda.synchronize()
     # gradients are sums of bf16-rounded products: max-abs bar scaled by the tensor's own magnitude

@@ -95,7 +95,7 @@ def test_rope_then_attention_matches_the_oracle_composition():
     L = torch.empty((B, Hq, n), device=U.DEV)
     sa.sa_fwd(desc, Qr, Kr, V, perm, Y, L)
     dQ, dK, dV = torch.full_like(Q, float("nan")), torch.full_like(K, float("nan")), torch.full_like(V, float("nan"))
-    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD), device=U.DEV, dtype=torch.uint8)
+    ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD),), 255, device=U.DEV, dtype=torch.uint8)
     sa.sa_bwd(desc, None, Qr, Kr, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
     sa.sa_rope(desc, dQ, dK, table, dQ, dK, inverse=1)
     torch.cuda.synchronize()
@@ -230,7 +230,7 @@ def test_bwd_rope_rejects_unsupported():
     xb = torch.zeros((1, 1, 8, 64), device=U.DEV, dtype=torch.bfloat16)
     L = torch.zeros((1, 1, 8), device=U.DEV)
     desc = sa.make_desc(1, 1, 1, 8, 64, 4)
-    ws = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE), device=U.DEV, dtype=torch.uint8)
+    ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE),), 255, device=U.DEV, dtype=torch.uint8)
     out = [torch.empty_like(xb) for _ in range(3)]
     with pytest.raises(sa.SaError) as e:   # no table
         sa.sa_bwd_rope(desc, xb, xb, xb, None, None, xb, L, xb, *out, ws)
