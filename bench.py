@@ -517,18 +517,21 @@ def main():
         _, bw_ms = time_side(lambda: sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, LSE, None, dYh,
                                              dQh, dKh, dVh, None, None, wsh), max(5, args.steps // 20), 2)
         other.update({"sa_bwd_headline_shape_ms": bw_ms})
-        # the training sequence with RoPE on original positions: sa_bwd on rotated Q, K followed by the inverse
-        # rotation of dQ and dK in memory, against sa_bwd_rope (Q rotated while staged, dQ and dK turned back in
-        # the epilogues of the two kernels)
+        # the training sequence with RoPE on original positions, from unrotated Q and rotated K (what a forward with
+        # the fused query rotation leaves): rotate Q in memory, sa_bwd, turn dQ and dK back in memory -- against
+        # sa_bwd_rope (Q rotated while staged, dQ and dK turned back in the epilogues of the two kernels).  Timed
+        # alternately; the forward that provides Y and LSE runs on the rotated rows.
         sa.sa_rope(desc, Q, K, table, Y2, Kr)
-        def bwd_then_inverse_rope():
+        sa.sa_fwd(desc, Y2, Kr, V, perm, Y, LSE)
+        def rope_bwd_inverse_rope():
+            sa.sa_rope(desc, Q, None, table, Y2, None)
             sa.sa_bwd(desc, None, Y2, Kr, V, perm, None, None, Y, None, LSE, None, dYh, dQh, dKh, dVh, None, None, wsh)
             sa.sa_rope(desc, dQh, dKh, table, dQh, dKh, inverse=1)
-        _, bu_ms = time_side(bwd_then_inverse_rope, max(5, args.steps // 20), 2)
         wsr = torch.empty(sa.sa_workspace_bytes(desc, sa.SA_OP_BWD_ROPE), device=dev, dtype=torch.uint8)
-        _, bf_ms = time_side(lambda: sa.sa_bwd_rope(desc, Q, Kr, V, perm, table, Y, LSE, dYh, dQh, dKh, dVh, wsr,
-                                                    dk_unrotated=1), max(5, args.steps // 20), 2)
-        other.update({"sa_bwd_plus_inverse_rope_ms": bu_ms, "sa_bwd_rope_ms": bf_ms})
+        bu_ms, bf_ms = time_pair(rope_bwd_inverse_rope,
+                                 lambda: sa.sa_bwd_rope(desc, Q, Kr, V, perm, table, Y, LSE, dYh, dQh, dKh, dVh, wsr,
+                                                        dk_unrotated=1), max(5, args.steps // 20), 2)
+        other.update({"rope_plus_sa_bwd_plus_inverse_rope_ms": bu_ms, "sa_bwd_rope_ms": bf_ms})
         del dYh, dQh, dKh, dVh, wsh, wsr, Y2, Kr, table
         # the decoding step that follows this prefill (Sec. 4.2): one new token per sequence over the whole
         # 32K-row cache of the same heads; and a batch of 16 sequences with 8K-row caches
