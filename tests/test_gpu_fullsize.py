@@ -277,3 +277,73 @@ def test_pretrain_fwdbwd_8k_gated_sampled_rows():
     for got, ref, what in ((dga, dga_r, "dgate_sa"), (dgl, dgl_r, "dgate_swa")):
         g = got[ri[:, 0], ri[:, 1], ri[:, 2]].cpu().numpy().astype(np.float64)
         U.assert_close(g, ref.reshape(m), "bf16", what + " rows", scale_abs=scale(ref))
+
+
+def test_pretrain_fwdbwd_8k_single_path_whole_tensors():
+    """The shape the backward's roofline block is quoted on (B=4, H=16, n=8192, d=64, w=256, one permutation shared by
+    the heads), single-path sa_fwd + sa_bwd in the launch configuration bench.py times: every element of Y, LSE, dQ,
+    dK and dV against the oracle (about ten seconds of CPU work)."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["pretrain_fwdbwd_8k"]
+    print("case fullsize whole tensors sa_fwd + sa_bwd pretrain_fwdbwd_8k", flush=True)
+    B, H, n, d = wl.B, wl.Hq, wl.n, wl.d
+    Q, K, V, dY = (gpu_normal((B, H, n, d), s) for s in (11, 12, 13, 14))
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    desc = U.sa_desc(wl, CIRC, 1)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, H, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+    ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD),), 255, device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    torch.cuda.synchronize()
+    Q64, K64, V64, dY64 = (host64(t) for t in (Q, K, V, dY))
+    oc = U.orc_desc(wl, CIRC, 1)
+    Yr, Lr = orc.sa_fwd(oc, Q64, K64, V64, perm_np)
+    U.assert_close(U.to_np64(Y), Yr, "bf16", "Y")
+    assert np.abs(L.cpu().numpy().astype(np.float64) - Lr).max() <= 4e-3, "LSE"
+    dQr, dKr, dVr = orc.sa_bwd(oc, Q64, K64, V64, perm_np, dY64)
+    for got, ref, what in ((dQ, dQr, "dQ"), (dK, dKr, "dK"), (dV, dVr, "dV")):
+        U.assert_close(U.to_np64(got), ref, "bf16", what, scale_abs=max(1.0, float(np.abs(ref).max())))
+
+
+def test_pretrain_fwdbwd_8k_gated_whole_tensors():
+    """Fourth benchmark configuration whole: gated SA + SWA forward and backward at B=4, H=16, n=8192, d=64, w=256 in
+    the launch configuration bench.py times, every element of Y, Y_sa, Y_swa, dQ, dK, dV and both gate gradients
+    against the oracle (the sampled-row test above names rows; this one leaves none out)."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["pretrain_fwdbwd_8k"]
+    print("case fullsize whole tensors gated fwd + bwd pretrain_fwdbwd_8k", flush=True)
+    B, H, n, d = wl.B, wl.Hq, wl.n, wl.d
+    Q, K, V, dY = (gpu_normal((B, H, n, d), s) for s in (21, 22, 23, 24))
+    ga = gpu_normal((B, H, n), 25, torch.float32)
+    gl = gpu_normal((B, H, n), 26, torch.float32)
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    dsa, dswa = U.sa_desc(wl, CIRC, 1), U.sa_desc(wl, ONE, 1)
+    Y, Ysa, Yswa = (torch.full_like(Q, float("nan")) for _ in range(3))
+    Lsa = torch.empty((B, H, n), device=U.DEV, dtype=torch.float32)
+    Lswa = torch.empty_like(Lsa)
+    wsf = torch.full((sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD),), 255, device=U.DEV, dtype=torch.uint8)
+    sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
+    dQ, dK, dV = (torch.full_like(Q, float("nan")) for _ in range(3))
+    dga, dgl = torch.full_like(ga, float("nan")), torch.full_like(gl, float("nan"))
+    ws = torch.full((sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_BWD),), 255, device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(dsa, dswa, Q, K, V, perm, ga, gl, Ysa, Yswa, Lsa, Lswa, dY, dQ, dK, dV, dga, dgl, ws)
+    torch.cuda.synchronize()
+    Q64, K64, V64, dY64, ga64, gl64 = (host64(t) for t in (Q, K, V, dY, ga, gl))
+    osa, oswa = U.orc_desc(wl, CIRC, 1), U.orc_desc(wl, ONE, 1)
+    f = orc.gated_sa_swa_fwd(osa, oswa, 0, Q64, K64, V64, perm_np, ga64, gl64)
+    U.assert_close(U.to_np64(Y), f["Y"], "bf16", "Y")
+    U.assert_close(U.to_np64(Ysa), f["Ysa"], "bf16", "Y_sa")
+    U.assert_close(U.to_np64(Yswa), f["Yswa"], "bf16", "Y_swa")
+    del f
+    ref = orc.gated_sa_swa_bwd(osa, oswa, 0, Q64, K64, V64, perm_np, ga64, gl64, dY64)
+    for got, r, what in ((dQ, ref[0], "dQ"), (dK, ref[1], "dK"), (dV, ref[2], "dV"), (dga, ref[3], "dgate_sa"),
+                         (dgl, ref[4], "dgate_swa")):
+        U.assert_close(U.to_np64(got), r, "bf16", what, scale_abs=max(1.0, float(np.abs(r).max())))
