@@ -347,3 +347,36 @@ def test_pretrain_fwdbwd_8k_gated_whole_tensors():
     for got, r, what in ((dQ, ref[0], "dQ"), (dK, ref[1], "dK"), (dV, ref[2], "dV"), (dga, ref[3], "dgate_sa"),
                          (dgl, ref[4], "dgate_swa")):
         U.assert_close(U.to_np64(got), r, "bf16", what, scale_abs=max(1.0, float(np.abs(r).max())))
+
+
+def test_qwen3_8b_prefill_32k_forward_backward_whole_tensors():
+    """The headline shape whole (B=1, 32 / 8 heads, n=32768, d=128, w=512): every element of Y, LSE, dQ, dK and dV of
+    sa_fwd + sa_bwd against the oracle (about twenty seconds of CPU work on the GPU machine's cores)."""
+    from oracle import binding as orc
+    from paper_2604_00754_amd import binding as sa
+    from paper_2604_00754_amd import synth
+    wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]
+    print("case fullsize whole tensors sa_fwd + sa_bwd qwen3_8b_prefill_32k", flush=True)
+    B, Hq, Hkv, n, d = wl.B, wl.Hq, wl.Hkv, wl.n, wl.d
+    Q, dY = gpu_normal((B, Hq, n, d), 31), gpu_normal((B, Hq, n, d), 34)
+    K, V = gpu_normal((B, Hkv, n, d), 32), gpu_normal((B, Hkv, n, d), 33)
+    perm_np = synth.permutations(1, 1, n)
+    perm = torch.from_numpy(perm_np).to(U.DEV)
+    desc = U.sa_desc(wl, CIRC, 1)
+    Y = torch.full_like(Q, float("nan"))
+    L = torch.full((B, Hq, n), float("nan"), device=U.DEV, dtype=torch.float32)
+    sa.sa_fwd(desc, Q, K, V, perm, Y, L)
+    dQ = torch.full_like(Q, float("nan"))
+    dK, dV = torch.full_like(K, float("nan")), torch.full_like(K, float("nan"))
+    ws = torch.full((sa.sa_workspace_bytes(desc, sa.SA_OP_BWD),), 255, device=U.DEV, dtype=torch.uint8)
+    sa.sa_bwd(desc, None, Q, K, V, perm, None, None, Y, None, L, None, dY, dQ, dK, dV, None, None, ws)
+    torch.cuda.synchronize()
+    Q64, K64, V64, dY64 = (host64(t) for t in (Q, K, V, dY))
+    od = U.orc_desc(wl, CIRC, 1)
+    Yr, Lr = orc.sa_fwd(od, Q64, K64, V64, perm_np)
+    U.assert_close(U.to_np64(Y), Yr, "bf16", "Y")
+    assert np.abs(L.cpu().numpy().astype(np.float64) - Lr).max() <= 4e-3, "LSE"
+    del Yr, Lr
+    dQr, dKr, dVr = orc.sa_bwd(od, Q64, K64, V64, perm_np, dY64)
+    for got, ref, what in ((dQ, dQr, "dQ"), (dK, dKr, "dK"), (dV, dVr, "dV")):
+        U.assert_close(U.to_np64(got), ref, "bf16", what, scale_abs=max(1.0, float(np.abs(ref).max())))
