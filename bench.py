@@ -355,6 +355,24 @@ def profile_side_op(sa, synth, dev, args):
         Lswa = torch.empty_like(Lsa)
         wsf = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATED_FWD), device=dev, dtype=torch.uint8)
         call = lambda: sa.gated_sa_swa_fwd(dsa, dswa, Q, K, V, perm, ga, gl, Y, Ysa, Yswa, Lsa, Lswa, wsf)
+    elif args.profile_op in ("gate_proj_fwd", "gate_proj_bwd"):
+        # the gate projections of Eq. 6 + Eq. 5 at d_model = H * d = 1024 over the pre-training shape's tokens
+        wl = synth.WORKLOADS["pretrain_fwdbwd_8k"]
+        g = torch.Generator(device=dev)
+        g.manual_seed(synth.BASE_SEED + 5)
+        rn = lambda shape, sc=1.0: (torch.randn(shape, device=dev, dtype=torch.float32, generator=g) * sc).to(torch.bfloat16)
+        dm = wl.Hq * wl.d
+        Ysa, Yswa, dY = (rn((wl.B, wl.Hq, wl.n, wl.d)) for _ in range(3))
+        Wsa, Wswa = rn((dm, dm), dm ** -0.5), rn((dm, dm), dm ** -0.5)
+        Y, Gsa, Gswa, dYsa, dYswa = (torch.empty_like(Ysa) for _ in range(5))
+        dWsa, dWswa = torch.empty_like(Wsa), torch.empty_like(Wswa)
+        dsa = sa.make_desc(wl.B, wl.Hq, wl.Hkv, wl.n, wl.d, wl.w, sa.SA_WIN_SYM_CIRCULAR, 1, sa.SA_BF16, 0.0, 1, 1)
+        wsg = torch.empty(sa.sa_workspace_bytes(dsa, sa.SA_OP_GATE_PROJ_BWD), device=dev, dtype=torch.uint8)
+        sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa)
+        if args.profile_op == "gate_proj_fwd":
+            call = lambda: sa.sa_gate_proj_fwd(dsa, Ysa, Yswa, Wsa, Wswa, Y, Gsa, Gswa)
+        else:
+            call = lambda: sa.sa_gate_proj_bwd(dsa, Ysa, Yswa, Wsa, Wswa, Gsa, Gswa, dY, dYsa, dYswa, dWsa, dWswa, wsg)
     else:
         wl, call, keep = backward_setup(sa, synth, dev, "pretrain_fwdbwd_8k" if args.profile_op == "sa_bwd"
                                         else "qwen3_8b_prefill_32k")
@@ -379,10 +397,12 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy before and between steps (a known-size kernel "
                          "for scaling the FETCH_SIZE / WRITE_SIZE counters; it also empties the caches)")
-    ap.add_argument("--profile-op", choices=["sa_fwd", "sa_bwd", "sa_bwd_headline", "gated_fwd"], default=None,
+    ap.add_argument("--profile-op", choices=["sa_fwd", "sa_bwd", "sa_bwd_headline", "gated_fwd", "gate_proj_fwd", "gate_proj_bwd"],
+                    default=None,
                     help="profiling runs: call this entry point --steps times (after --warmup) and print a short JSON "
                          "line; sa_fwd = the headline step, sa_bwd / gated_fwd = the pre-training shape B4 H16 n8192 "
-                         "d64 w256, sa_bwd_headline = the backward at the headline shape; honours --calibrate-copy")
+                         "d64 w256, sa_bwd_headline = the backward at the headline shape, gate_proj_fwd / gate_proj_bwd = the gate "
+                         "projections at d_model 1024 over the same tokens; honours --calibrate-copy")
     ap.add_argument("--table3", action="store_true",
                     help="instead of the headline step, run the sequence-length sweep of Sec. 4.3 / Table 3 "
                          "(SA, SWA, gated, full attention; forward + backward) and print it as one JSON line")
@@ -402,7 +422,7 @@ def main():
     if args.table3:
         print(json.dumps(table3_sweep(sa, synth, dev)))
         return
-    if args.profile_op in ("sa_bwd", "sa_bwd_headline", "gated_fwd"):
+    if args.profile_op in ("sa_bwd", "sa_bwd_headline", "gated_fwd", "gate_proj_fwd", "gate_proj_bwd"):
         print(json.dumps(profile_side_op(sa, synth, dev, args)))
         return
     wl = synth.WORKLOADS["qwen3_8b_prefill_32k"]

@@ -73,12 +73,14 @@ __global__ __launch_bounds__(GNT, 2) void gate_proj_fwd_bf16_kernel(const GatePr
   // loader: 128 rows x 8 chunks of 16 bytes per operand tile, 4 chunks per thread and operand
   const int lrow = tid >> 3, lchunk = tid & 7;  // rows lrow + 32*j
   u32x4 areg[4], wreg[4];
-  // Forward: the contraction steps are taken in rotated order, ending with the two that cover the workgroup's own
-  // 128 output features, so that the token tiles left in the two buffers are the Y_x values Eq. 5 needs at the
-  // output positions (the epilogue reads them from LDS instead of from memory).
-  const int krot = MODE == GP_FORWARD ? (o0 / TK + 2) % nk : 0;  // (dm is a multiple of TN = 2 TK: nk >= 2)
+  // Forward: the two contraction steps that cover the workgroup's own 128 output features are taken last, so that
+  // the token tiles left in the two buffers are the Y_x values Eq. 5 needs at the output positions (the epilogue
+  // reads them from LDS instead of from memory).  The other steps keep their order: the workgroups that share a
+  // token tile (the feature tiles of one token tile run side by side) then walk it nearly in step and find each
+  // other's rows in L2 (fully rotated orders kept the whole tile of every group alive there: 4 x the fetches).
+  const int own = MODE == GP_FORWARD ? o0 / TK : nk;  // (dm is a multiple of TN = 2 TK: nk >= 2)
   auto load_tiles = [&](const bf16_t* Yx, const bf16_t* Wx, int step) {
-    const int kk = step + krot < nk ? step + krot : step + krot - nk;
+    const int kk = MODE != GP_FORWARD ? step : (step < nk - 2 ? (step < own ? step : step + 2) : own + step - (nk - 2));
     const int k0 = kk * TK, h = k0 / D, e0 = k0 % D;
     const bf16_t* abase = Yx + ((size_t)b * H + h) * n * (size_t)D + e0 + lchunk * 8;
     const bf16_t* wbase = Wx + (size_t)k0 + lchunk * 8;
